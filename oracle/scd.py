@@ -1,0 +1,299 @@
+"""Speculative Coupled Decoding, maximal-coupling variant (oracle side; test
+infrastructure only).
+
+Two forms of the same decode loop are written out:
+
+  * ScdOracle / decode(): the "efficient" form (appendix "Algorithms",
+    Alg. SCD(pi_MC)): after the target model has been evaluated on the window,
+    ONE Modified-Rejection-Sampling call per window position, without break;
+    the index of the first rejection decides how many tokens are emitted.  Left
+    of it the calls are the speculative verification, at it the call is the
+    residual resample, right of it the calls are the coupled redraft of the
+    next iteration's draft tokens.
+  * decode_sequential(): the pedagogical form (Sec. 4.1, Alg. "Pseudo code for
+    our SCD"): a Drafting phase that re-couples every not-yet-verified draft
+    with MRS, an Evaluate phase, and a sequential Verify phase that breaks at
+    the first rejection.  Sec. 4.3 states that the two are the same operation;
+    with draws keyed on (position, iteration) they emit identical tokens.
+
+Readings fixed here (the paper's loops are ambiguous about them):
+  * the window is exactly L positions [i, i+L) clipped to the sequence end
+    (Lw = min(L, N-i)); a rejection at window offset r emits r+1 tokens
+    (r accepted drafts + the resampled token), no rejection emits Lw tokens;
+  * a position that has never been evaluated carries the draft distribution
+    Uniform(allowed ids) and a draft token drawn from it ("p <- Random(),
+    X ~ p" in the algorithms' initialisation);
+  * the iteration index in the key of a draw is the iteration whose Evaluate
+    produced the target distribution P of that MRS call;
+  * tokens are handled as offsets 0..|A|-1 into the allowed id range
+    [v_lo, v_hi); emitted tokens are v_lo + offset.
+"""
+from dataclasses import dataclass, field
+import numpy as np
+
+from . import philox
+from . import logits as lg
+from . import mrs as mrs_mod
+
+
+@dataclass
+class ScdConfig:
+    B: int = 1
+    L: int = 8
+    N: int = 64
+    V: int = 1024
+    v_lo: int = 0
+    v_hi: int = -1           # -1 => V
+    top_k: int = 0           # 0 => off
+    temperature: float = 1.0
+    cfg_lambda: float = 0.0  # 0 => no CFG
+    seed: int = 0
+
+    def __post_init__(self):
+        if self.v_hi < 0:
+            self.v_hi = self.V
+
+    @property
+    def n_allowed(self):
+        return self.v_hi - self.v_lo
+
+
+def _ambiguous_ids(z, thr, top_k, tol_z):
+    """Ids whose membership in the top-k set could flip under a logit
+    perturbation of tol_z: strictly different from thr but within tol_z."""
+    if top_k <= 0 or top_k >= z.shape[-1]:
+        return np.zeros(0, dtype=np.int64)
+    d = np.abs(z.astype(np.float64) - np.float64(thr))
+    return np.nonzero((d > 0) & (d <= tol_z))[0]
+
+
+class ScdOracle:
+    """State machine of the vectorised form.  One step = evaluate() (turn the
+    processed-logit rows of the window into distributions), sample() (one MRS
+    per window position) and commit() (emit, slide, re-initialise)."""
+
+    def __init__(self, cfg: ScdConfig, tol=1e-5):
+        self.cfg = cfg
+        self.tol = tol
+        B, L, N = cfg.B, cfg.L, cfg.N
+        self.i = [0] * B                      # accepted-prefix pointer
+        self.t = [0] * B                      # iterations done (= NFE)
+        self.X = np.full((B, N + L), -1, dtype=np.int64)      # current draft per position
+        self.age = np.zeros((B, N + L), dtype=np.int64)       # evaluations so far
+        self.q = [dict() for _ in range(B)]   # pos -> fp64 row of the draft distribution
+        self.out = np.full((B, N), -1, dtype=np.int64)
+        self.accept_hist = [[] for _ in range(B)]
+        self.positions_verified = 0
+        for b in range(B):
+            for j in range(min(L, N)):
+                self._init_position(b, j)
+
+    # -- helpers -----------------------------------------------------------
+    def _init_position(self, b, j):
+        self.X[b, j] = philox.init_token(self.cfg.seed, b, j, self.cfg.n_allowed)
+        self.age[b, j] = 0
+        self.q[b].pop(j, None)
+
+    def window(self, b):
+        i = self.i[b]
+        return i, max(0, min(self.cfg.L, self.cfg.N - i))
+
+    def done(self):
+        return all(i >= self.cfg.N for i in self.i)
+
+    def draft_row(self, b, j):
+        """Draft distribution of position j: stored p of its last evaluation,
+        or uniform over the allowed ids if never evaluated."""
+        if j in self.q[b]:
+            return self.q[b][j]
+        n = self.cfg.n_allowed
+        # fp32(1/n) is what an fp32 implementation holds; keep that value.
+        return np.full(n, np.float64(np.float32(1.0) / np.float32(n)))
+
+    # -- phase 1: distributions ---------------------------------------------
+    def evaluate(self, z_rows, keep_override=None):
+        """z_rows[b]: fp32 [Lw_b, |A|] processed logits of the window
+        (after CFG, mask, temperature).  Returns plan[b][s] =
+        dict(p, thr, lse, nkept, ambiguous)."""
+        cfg = self.cfg
+        plan = []
+        for b in range(cfg.B):
+            i, Lw = self.window(b)
+            rows = []
+            for s in range(Lw):
+                z = np.asarray(z_rows[b][s], dtype=np.float32)
+                thr = lg.topk_threshold(z, cfg.top_k)
+                tol_z = self.tol * max(1.0, abs(float(thr))) * (1.0 + 2.0 * cfg.cfg_lambda) \
+                    if np.isfinite(thr) else 0.0
+                amb = _ambiguous_ids(z, thr, cfg.top_k, tol_z)
+                keep = z >= thr
+                ov = (keep_override or {}).get((b, i + s))
+                if ov:
+                    for v, kv in ov.items():
+                        assert v in amb, "membership override outside the ambiguous set"
+                        keep[v] = kv
+                z64 = z.astype(np.float64)
+                m = z64[keep].max()
+                e = np.where(keep, np.exp(z64 - m), 0.0)
+                ssum = e.sum()
+                rows.append(dict(p=e / ssum, thr=thr, lse=m + np.log(ssum),
+                                 nkept=int(keep.sum()), ambiguous=amb))
+            plan.append(rows)
+        return plan
+
+    # -- phase 2: one MRS per window position ------------------------------
+    def sample(self, plan, accept_override=None, resid_override=None):
+        """Vectorised MRS (Alg. SCD(pi_MC), the parallel-for over the window).
+        Overrides force a decision and are legal only on flagged draws."""
+        cfg = self.cfg
+        res = []
+        for b in range(cfg.B):
+            i, Lw = self.window(b)
+            t = self.t[b]
+            rows = []
+            for s in range(Lw):
+                j = i + s
+                p = plan[b][s]["p"]
+                q = self.draft_row(b, j)
+                x = int(self.X[b, j])
+                u = philox.uniform_scalar(cfg.seed, b, j, t, philox.STREAM_ACCEPT)
+                U_fn = lambda b=b, j=j, t=t: philox.uniform_per_vocab(
+                    cfg.seed, b, j, t, philox.STREAM_RESID, cfg.n_allowed)
+                r = mrs_mod.mrs(p, q, x, u, U_fn, self.tol)
+                r["u"] = u
+                key = (b, j)
+                if accept_override and key in accept_override and accept_override[key] != r["k"]:
+                    assert r["flag_accept"], "accept override on an unflagged draw"
+                    forced = accept_override[key]
+                    if forced:
+                        r.update(y=x, k=1, flag_resid=False)
+                    else:
+                        U = U_fn()
+                        w, _ = mrs_mod.residual_race(p, q, U)
+                        r.update(y=w, k=0, flag_resid=mrs_mod.residual_flag(p, q, U, w, self.tol))
+                if resid_override and key in resid_override and r["k"] == 0 \
+                        and resid_override[key] != r["y"]:
+                    assert r["flag_resid"], "residual override on an unflagged draw"
+                    r["y"] = int(resid_override[key])
+                rows.append(r)
+            res.append(rows)
+        return res
+
+    # -- phase 3: first rejection, emit, slide -----------------------------
+    def commit(self, plan, res):
+        cfg = self.cfg
+        accept_len = []
+        for b in range(cfg.B):
+            i, Lw = self.window(b)
+            if Lw == 0:
+                accept_len.append(0)
+                continue
+            first_rej = Lw
+            for s in range(Lw):
+                if res[b][s]["k"] == 0:
+                    first_rej = s
+                    break
+            a = min(first_rej + 1, Lw)
+            for s in range(a):
+                self.out[b, i + s] = cfg.v_lo + res[b][s]["y"]
+            for s in range(a, Lw):                    # survivors: coupled redraft
+                j = i + s
+                self.X[b, j] = res[b][s]["y"]
+                self.q[b][j] = plan[b][s]["p"]
+                self.age[b, j] += 1
+            for s in range(a):                        # retired positions
+                self.q[b].pop(i + s, None)
+            for j in range(i + Lw, min(i + a + cfg.L, cfg.N)):   # entering positions
+                self._init_position(b, j)
+            self.positions_verified += Lw
+            self.i[b] = i + a
+            self.t[b] += 1
+            self.accept_hist[b].append(a)
+            accept_len.append(a)
+        return accept_len
+
+    def step(self, z_rows):
+        plan = self.evaluate(z_rows)
+        res = self.sample(plan)
+        return plan, res, self.commit(plan, res)
+
+
+def decode(cfg: ScdConfig, model, tol=1e-5):
+    """Run the vectorised form to the end.  model(b, i, Lw, tokens, t, age) ->
+    fp32 [Lw, |A|] processed logits for positions i..i+Lw-1, where tokens[j] is
+    the emitted token offset for j < i and the current draft for i <= j < i+Lw
+    (row s may depend on tokens[:i+s] only), and age[s] counts the earlier
+    evaluations of position i+s."""
+    o = ScdOracle(cfg, tol)
+    while not o.done():
+        z_rows = []
+        for b in range(cfg.B):
+            i, Lw = o.window(b)
+            if Lw == 0:
+                z_rows.append(None)
+                continue
+            toks = np.concatenate([o.out[b, :i] - cfg.v_lo, o.X[b, i:i + Lw]])
+            z_rows.append(model(b, i, Lw, toks, o.t[b], o.age[b, i:i + Lw].copy()))
+        o.step(z_rows)
+    return o
+
+
+def decode_sequential(cfg: ScdConfig, model, tol=1e-5):
+    """Pedagogical form (Sec. 4.1): Drafting / Evaluate / Verify-with-break.
+    Returns (out [B, N], nfe [B], accept lengths per sequence)."""
+    B, L, N, n = cfg.B, cfg.L, cfg.N, cfg.n_allowed
+    uniform = np.full(n, np.float64(np.float32(1.0) / np.float32(n)))
+    out = np.full((B, N), -1, dtype=np.int64)
+    nfe, hist = [], []
+    for b in range(B):
+        X = {}          # draft token per position
+        p_new = {}      # p^{t}   : newest evaluated distribution per position
+        p_old = {}      # p^{t-1} : the one before (uniform if none)
+        t_new = {}      # iteration whose Evaluate produced p_new
+        age = {}
+        for j in range(min(L, N)):
+            X[j] = philox.init_token(cfg.seed, b, j, n)
+        i, t, h = 0, 0, []
+        while i < N:
+            Lw = min(L, N - i)
+            # Drafting: re-couple drafts whose newest distribution has not
+            # been used on them yet (positions right of the last rejection).
+            for j in range(i, i + Lw):
+                if j in p_new:
+                    u = philox.uniform_scalar(cfg.seed, b, j, t_new[j], philox.STREAM_ACCEPT)
+                    U_fn = lambda j=j: philox.uniform_per_vocab(
+                        cfg.seed, b, j, t_new[j], philox.STREAM_RESID, n)
+                    r = mrs_mod.mrs(p_new[j], p_old.get(j, uniform), X[j], u, U_fn, tol)
+                    X[j] = r["y"]
+                    p_old[j] = p_new.pop(j)
+            # Evaluate
+            toks = np.array([out[b, j] - cfg.v_lo for j in range(i)] +
+                            [X[j] for j in range(i, i + Lw)], dtype=np.int64)
+            ages = np.array([age.get(j, 0) for j in range(i, i + Lw)])
+            z = model(b, i, Lw, toks, t, ages)
+            for s in range(Lw):
+                j = i + s
+                p_new[j], _, _ = lg.distribution(z[s], cfg.top_k)
+                t_new[j] = t
+                age[j] = age.get(j, 0) + 1
+            # Verify, sequentially, break at the first rejection
+            j = i
+            while j < i + Lw:
+                u = philox.uniform_scalar(cfg.seed, b, j, t, philox.STREAM_ACCEPT)
+                U_fn = lambda j=j: philox.uniform_per_vocab(
+                    cfg.seed, b, j, t, philox.STREAM_RESID, n)
+                r = mrs_mod.mrs(p_new[j], p_old.get(j, uniform), X[j], u, U_fn, tol)
+                out[b, j] = cfg.v_lo + r["y"]
+                for dct in (p_new, p_old, X):
+                    dct.pop(j, None)
+                j += 1
+                if r["k"] == 0:
+                    break
+            a = j - i
+            for jn in range(i + Lw, min(i + a + L, N)):
+                X[jn] = philox.init_token(cfg.seed, b, jn, n)
+            i, t = j, t + 1
+            h.append(a)
+        nfe.append(t)
+        hist.append(h)
+    return out, nfe, hist

@@ -1,0 +1,109 @@
+"""Pins for the oracle's LM head and logit processors (CPU only): brute force
+on tiny inputs with exact rational arithmetic, library routines on the special
+cases that reduce to them, and invariants."""
+from fractions import Fraction
+
+import numpy as np
+from scipy import special
+
+from oracle import logits as lg
+from paper_2510_24211_amd.workload import f32_to_bf16_bits
+
+
+def _bf16_fraction(bits):
+    f = np.array([bits], dtype=np.uint16).astype(np.uint32) << np.uint32(16)
+    return Fraction(float(f.view(np.float32)[0]))
+
+
+def test_bf16_decode_matches_float_semantics():
+    x = np.array([0.0, 1.0, -2.5, 0.02, 3.140625, -1e-3], dtype=np.float32)
+    bits = f32_to_bf16_bits(x)
+    back = lg.bf16_bits_to_f64(bits)
+    # bf16 keeps 8 significant bits: relative error <= 2^-9, exact on short values
+    assert np.all(np.abs(back - x) <= np.abs(x) * 2.0 ** -9)
+    assert back[1] == 1.0 and back[2] == -2.5 and back[4] == 3.140625
+
+
+def test_lm_head_brute_force_rational():
+    g = np.random.default_rng(0)
+    M, V, d = 3, 5, 16
+    h = f32_to_bf16_bits(g.standard_normal((M, d)).astype(np.float32))
+    W = f32_to_bf16_bits((g.standard_normal((V, d)) * 0.02).astype(np.float32))
+    got = lg.lm_head(h, W)
+    assert got.dtype == np.float32 and got.shape == (M, V)
+    for m in range(M):
+        for v in range(V):
+            exact = sum(_bf16_fraction(h[m, k]) * _bf16_fraction(W[v, k]) for k in range(d))
+            assert got[m, v] == np.float32(float(exact))   # transposed operand or wrong axis fails
+
+
+def test_cfg_combine_roundings_and_closed_cases():
+    c = np.array([1.0, 0.1, -3.3, 7.0], dtype=np.float32)
+    u = np.array([1.0, 0.3, 2.2, -1.0], dtype=np.float32)
+    # lambda = 0 returns c exactly; u == 0 gives (1+lambda) c
+    assert np.array_equal(lg.cfg_combine(c, u, 0.0), c)
+    assert np.array_equal(lg.cfg_combine(c, np.zeros_like(c), 3.0), np.float32(4.0) * c)
+    # exact dyadic values: (1+3)*1 - 3*1 = 1 ; 4*7 - 3*(-1) = 31
+    z = lg.cfg_combine(c, u, 3.0)
+    assert z[0] == 1.0 and z[3] == 31.0
+    # the three roundings, spelled with Fractions
+    for ci, ui, zi in zip(c, u, z):
+        a = np.float32(float(Fraction(float(ci)) * 4))
+        b = np.float32(float(Fraction(float(ui)) * 3))
+        assert zi == np.float32(float(Fraction(float(a)) - Fraction(float(b))))
+    # guidance pushes away from u: sign convention (1+l)c - l u, not l c - (l-1) u
+    assert lg.cfg_combine(np.float32([1.0]), np.float32([0.0]), 3.0)[0] == 4.0
+
+
+def test_temperature():
+    z = np.array([1.0, -2.0, 0.3], dtype=np.float32)
+    assert np.array_equal(lg.apply_temperature(z, 1.0), z)
+    assert np.array_equal(lg.apply_temperature(z, 2.0), z / np.float32(2.0))
+    # sharper for tau < 1
+    p_hot, _ = lg.softmax_kept(lg.apply_temperature(z, 0.5), -np.inf)
+    p_one, _ = lg.softmax_kept(z, -np.inf)
+    assert p_hot.max() > p_one.max()
+
+
+def test_softmax_without_topk_is_library_softmax():
+    g = np.random.default_rng(1)
+    z = (g.standard_normal(1000) * 3).astype(np.float32)
+    p, thr, lse = lg.distribution(z, 0)
+    assert thr == -np.inf
+    np.testing.assert_allclose(p, special.softmax(z.astype(np.float64)), rtol=1e-13)
+    np.testing.assert_allclose(lse, special.logsumexp(z.astype(np.float64)), rtol=1e-14)
+    # K = |A| keeps everything as well
+    p2, thr2, _ = lg.distribution(z, z.size)
+    assert thr2 == z.min()
+    np.testing.assert_allclose(p2, p, rtol=1e-13)
+
+
+def test_topk_brute_force_and_ties():
+    g = np.random.default_rng(2)
+    for n, K in [(10, 3), (50, 1), (50, 49), (257, 100)]:
+        z = g.standard_normal(n).astype(np.float32)
+        thr = lg.topk_threshold(z, K)
+        assert (z > thr).sum() == K - 1 and (z >= thr).sum() == K      # distinct values
+        p, _ = lg.softmax_kept(z, thr)
+        keep = np.argsort(-z)[:K]
+        want = np.zeros(n)
+        want[keep] = special.softmax(z[keep].astype(np.float64))
+        np.testing.assert_allclose(p, want, rtol=1e-13, atol=0)
+        assert abs(p.sum() - 1) < 1e-14 and (p > 0).sum() == K
+    # ties at the threshold are all kept
+    z = np.array([5, 3, 3, 3, 1, 0], dtype=np.float32)
+    thr = lg.topk_threshold(z, 2)
+    assert thr == 3.0
+    p, _ = lg.softmax_kept(z, thr)
+    assert (p > 0).sum() == 4
+    # K larger than the row
+    assert lg.topk_threshold(z, 100) == 0.0
+
+
+def test_lse_consistency():
+    g = np.random.default_rng(3)
+    z = (g.standard_normal(300) * 4).astype(np.float32)
+    p, thr, lse = lg.distribution(z, 40)
+    keep = z >= thr
+    np.testing.assert_allclose(p[keep], np.exp(z[keep].astype(np.float64) - lse), rtol=1e-12)
+    assert np.all(p[~keep] == 0)
