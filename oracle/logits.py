@@ -22,15 +22,17 @@ def bf16_bits_to_f64(u16):
     return (u16.astype(np.uint32) << np.uint32(16)).view(np.float32).astype(np.float64)
 
 
-def lm_head(h_bits, w_bits):
+def lm_head(h_bits, w):
     """logit[m, v] = sum_k h[m, k] * W[v, k]  (the last linear layer of the
     target model; "Evaluate" step of Alg. 2 / Alg. 3).
 
-    h_bits [M, d] and w_bits [V, d] are bf16 bit patterns.  fp64 accumulate,
+    h_bits [M, d]: bf16 bit patterns.  w [V, d]: bf16 bit patterns (uint16), or
+    the same matrix already decoded to float64 by bf16_bits_to_f64 (callers
+    that evaluate many windows against one W decode it once).  fp64 accumulate,
     one rounding to fp32."""
     h = bf16_bits_to_f64(h_bits)
-    w = bf16_bits_to_f64(w_bits)
-    return (h @ w.T).astype(np.float32)
+    w64 = w if w.dtype == np.float64 else bf16_bits_to_f64(w)
+    return (h @ w64.T).astype(np.float32)
 
 
 def cfg_combine(c, u, lam):
@@ -58,13 +60,13 @@ def process_logits(c, u, lam, tau):
 
 
 def topk_threshold(z, top_k):
-    """K-th largest value of the row (K = min(top_k, len)); -inf when top-k is
-    off (top_k == 0).  The kept set is {v : z_v >= threshold}: every value tied
-    with the K-th is kept."""
+    """K-th largest value of the row; -inf when nothing is filtered (top-k off,
+    i.e. top_k == 0, or K >= row length).  The kept set is
+    {v : z_v >= threshold}: every value tied with the K-th is kept."""
     z = np.asarray(z, dtype=np.float32)
     n = z.shape[-1]
     if top_k <= 0 or top_k >= n:
-        return np.float32(-np.inf) if top_k <= 0 else np.float32(z.min())
+        return np.float32(-np.inf)
     srt = np.sort(z)[::-1]
     return np.float32(srt[top_k - 1])
 

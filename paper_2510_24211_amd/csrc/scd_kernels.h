@@ -1,0 +1,98 @@
+// Host-callable launchers of the gfx950 kernels behind the C ABI in
+// include/scd.h.  Plain pointers and sizes only; every launcher enqueues on
+// the given stream and returns hipGetLastError().
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace scd {
+
+// ---- LM head + CFG combine + temperature --------------------------------
+struct LmHeadArgs {
+  const uint16_t* h;    // bf16 [B, C, L, d]
+  const uint16_t* W;    // bf16 [n, d]: first allowed row of the weight matrix
+  float* z;             // fp32 [(2,) B, L, n]
+  const int32_t* pos;   // [B] or null: row s is stored at ring slot (pos[b]+s) % L
+  const int32_t* iter;  // [B] or null: store into half (iter[b] & 1) of z
+  size_t parity_stride; // floats between the two halves of z
+  int B, C, L, N, d, n;
+  float lam, one_plus_lam, tau;
+};
+hipError_t launch_lm_head(const LmHeadArgs& a, hipStream_t s);
+
+// ---- top-k threshold + softmax normaliser -------------------------------
+struct SelectArgs {
+  const float* z;       // rows of n floats
+  size_t parity_stride; // floats between the two halves (ring mode)
+  const int32_t* pos;   // ring mode: [B]; null => plain mode, row r at z + r*n
+  const int32_t* iter;  // ring mode: [B]
+  float* thr;           // plain: [rows]; ring: [2, B, L]
+  float* lse;
+  int32_t* nkept;
+  int32_t* flags;       // numeric-fault bits (may be null)
+  int rows;             // plain mode: number of rows; ring mode: B*L
+  int B, L, N, n, top_k;
+};
+hipError_t launch_select(const SelectArgs& a, hipStream_t s);
+
+// ---- vectorised Modified Rejection Sampling ------------------------------
+struct MrsArgs {
+  const float* z_cur;   // plain: [B, L, n]; ring: base of [2, B, L, n]
+  const float* z_prev;  // plain: [B, L, n]; ring: unused
+  size_t parity_stride; // ring: floats between the halves of z
+  const float* thr_cur; // plain: [B*L];   ring: base of [2, B, L]
+  const float* lse_cur;
+  const float* thr_prev;
+  const float* lse_prev;
+  const int32_t* x;     // plain: [B, L] window order; ring: [B, L] by slot
+  const uint8_t* fresh; // plain: [B, L] or null
+  const int32_t* age;   // ring: [B, L] by slot (fresh <=> age == 0)
+  const int32_t* pos;   // [B]
+  const int32_t* iter;  // ring: [B]; plain: null (iter_scalar is used)
+  int iter_scalar;
+  int ring;
+  int32_t* y;           // [B, L] window order
+  uint8_t* k;           // [B, L] window order
+  float* px;            // [B, L] or null
+  float* qx;            // [B, L] or null
+  int B, L, N, n;
+  uint64_t seed;
+};
+hipError_t launch_mrs(const MrsArgs& a, hipStream_t s);
+
+// ---- first rejection, emit, slide -----------------------------------------
+struct CommitArgs {
+  const uint8_t* k;     // [B, L]
+  const int32_t* y;     // [B, L]
+  int32_t* pos;         // [B]  (read; advanced only when slide != 0)
+  int32_t* iter;        // [B]  (slide only)
+  int32_t* X;           // [B, L] ring (slide only)
+  int32_t* age;         // [B, L] ring (slide only)
+  int32_t* verified;    // [B] (slide only)
+  int32_t* accept_len;  // [B]
+  int32_t* out;         // [B, N]
+  int slide;
+  int B, L, N, n, v_lo;
+  uint64_t seed;
+};
+hipError_t launch_commit(const CommitArgs& a, hipStream_t s);
+
+// ---- state initialisation / logits copy-in --------------------------------
+struct ResetArgs {
+  int32_t* pos; int32_t* iter; int32_t* X; int32_t* age; int32_t* out; int32_t* accept_len;
+  int32_t* verified; int32_t* flags;
+  int B, L, N, n;
+  uint64_t seed;
+};
+hipError_t launch_reset(const ResetArgs& a, hipStream_t s);
+
+struct CopyInArgs {
+  const float* src;     // [B, L, n] window order
+  float* z;             // [2, B, L, n]
+  size_t parity_stride;
+  const int32_t* pos; const int32_t* iter;
+  int B, L, N, n;
+};
+hipError_t launch_copy_in(const CopyInArgs& a, hipStream_t s);
+
+}  // namespace scd

@@ -1,0 +1,237 @@
+"""Lock-step driver for the GPU parity tests: runs the HIP path (through the C
+ABI) and the CPU oracle side by side on the same seeded inputs, one decode
+iteration at a time, and compares everything the iteration produces.
+
+Integer results (tokens, accept bits, accept lengths, positions, ages,
+thresholds' kept-set sizes) must be identical, except on draws the oracle flags
+as numerically fragile (|u - p/q| < 1e-5; a residual race that a 1e-5 relative
+perturbation could flip; a top-k boundary closer than the logit tolerance).  On
+a flagged draw that differs the oracle adopts the GPU's decision, the event is
+counted, and both continue from the same state.  Any unflagged difference
+fails.
+
+Floating-point results: processed logits within 2e-3 relative (bf16 GEMM bar;
+the observed error is orders of magnitude lower and is recorded), log
+normalisers within `lse_tol`, p(x)/q(x) within `prob_rtol`.
+"""
+import numpy as np
+import torch
+
+from oracle import logits as lg
+from oracle import scd as oscd
+from paper_2510_24211_amd import binding as B
+from paper_2510_24211_amd import workload as wl
+
+
+def bf16_tensor(bits_np, device):
+    return torch.from_numpy(bits_np.view(np.int16)).to(device).view(torch.bfloat16)
+
+
+class LockStep:
+    def __init__(self, w: wl.Workload, device="cuda:0", check_logits=True):
+        self.w = w
+        self.device = device
+        self.check_logits = check_logits
+        self.cfg_c = B.config_from_workload(w)
+        self.gpu = B.Scd(self.cfg_c, device)
+        self.state = self.gpu.alloc_state()
+        self.gpu.reset(self.state)
+        self.ocfg = oscd.ScdConfig(B=w.B, L=w.L, N=w.N, V=w.V, v_lo=w.v_lo, v_hi=w.v_hi,
+                                   top_k=w.top_k, temperature=w.temperature,
+                                   cfg_lambda=w.cfg_lambda, seed=w.seed)
+        self.oracle = oscd.ScdOracle(self.ocfg)
+        self.n = w.n_allowed
+        if w.d > 0:
+            W = wl.lm_head_weight(w)
+            self.W_gpu = bf16_tensor(W, device)
+            self.W64 = lg.bf16_bits_to_f64(W[w.v_lo:w.v_hi])
+            del W
+            self.table = wl.HiddenTable(w)
+        else:
+            self.toy = wl.ToyLogits(w)
+        f = self.gpu.state_field
+        self.v = {name: f(self.state, fid) for name, fid in [
+            ("pos", B.F_POS), ("iter", B.F_ITER), ("X", B.F_X), ("age", B.F_AGE), ("out", B.F_OUT),
+            ("acc", B.F_ACCEPT), ("y", B.F_Y), ("k", B.F_K), ("px", B.F_PX), ("qx", B.F_QX),
+            ("thr", B.F_THR), ("lse", B.F_LSE), ("nkept", B.F_NKEPT), ("z", B.F_Z),
+            ("verified", B.F_VERIFIED)]}
+        self.stats = dict(steps=0, draws=0, flag_accept=0, flag_resid=0, flag_topk=0,
+                          adopt_accept=0, adopt_resid=0, adopt_topk=0,
+                          max_logit_abs=0.0, max_logit_rel=0.0, max_lse_abs=0.0, max_prob_rel=0.0)
+        lam = w.cfg_lambda
+        self.logit_tol = 1e-5 * (1 + 2 * lam)
+        self.lse_tol = 1e-6 if w.d == 0 else 2e-5 * (1 + 2 * lam)
+        self.prob_rtol = 4e-6 if w.d == 0 else 1e-4 * (1 + 2 * lam)
+        self.check_initial_state()
+
+    # ------------------------------------------------------------------
+    def check_initial_state(self):
+        w, o = self.w, self.oracle
+        X = self.v["X"].cpu().numpy().reshape(w.B, w.L)
+        for b in range(w.B):
+            for j in range(min(w.L, w.N)):
+                assert X[b, j] == o.X[b, j], "initial draft differs"
+        assert (self.v["out"].cpu().numpy() == -1).all()
+
+    def _windows(self):
+        o, w = self.oracle, self.w
+        ages = [[int(o.age[b, o.i[b] + s]) if o.i[b] + s < w.N else 0 for s in range(w.L)]
+                for b in range(w.B)]
+        return list(o.i), ages
+
+    def step(self):
+        w, o, st, v = self.w, self.oracle, self.stats, self.v
+        Bn, L, n = w.B, w.L, self.n
+        i_b, ages = self._windows()
+        t_b = list(o.t)
+        lives = [o.window(b)[1] for b in range(Bn)]
+        # ---- the same input bytes to both sides -----------------------------
+        if w.d > 0:
+            h = self.table.window(i_b, ages)                       # [B, C, L, d] bf16 bits
+            self.gpu.step(bf16_tensor(h, self.device), self.W_gpu, self.state)
+            z_rows = []
+            for b in range(Bn):
+                Lw = lives[b]
+                if Lw == 0:
+                    z_rows.append(None)
+                    continue
+                c = lg.lm_head(h[b, 0, :Lw], self.W64)
+                u = lg.lm_head(h[b, 1, :Lw], self.W64) if w.C == 2 else None
+                z_rows.append(lg.process_logits(c, u, w.cfg_lambda, w.temperature))
+        else:
+            z = self.toy.window(i_b, ages)                         # [B, L, n] fp32
+            self.gpu.step_logits(torch.from_numpy(z).to(self.device), self.state)
+            z_rows = [lg.process_logits(z[b, :lives[b]], None, 0.0, w.temperature)
+                      if lives[b] else None for b in range(Bn)]
+        rc, flags = self.gpu.status(self.state)
+        assert rc == B.SCD_OK, (rc, flags)
+
+        # ---- download what the step produced --------------------------------
+        g = {k: v[k].cpu().numpy() for k in ("pos", "iter", "X", "age", "acc", "y", "k", "px",
+                                             "qx", "thr", "lse", "nkept", "verified")}
+        g["thr"] = g["thr"].reshape(2, Bn, L)
+        g["lse"] = g["lse"].reshape(2, Bn, L)
+        g["nkept"] = g["nkept"].reshape(2, Bn, L)
+        zg = v["z"].view(2, Bn, L, n)
+
+        # ---- distributions: logits, threshold, normaliser --------------------
+        keep_override = {}
+        amb_rows = []
+        plan = o.evaluate(z_rows)
+        for b in range(Bn):
+            par = t_b[b] & 1
+            for s in range(lives[b]):
+                slot = (i_b[b] + s) % L
+                row = plan[b][s]
+                zo = z_rows[b][s]
+                if self.check_logits:
+                    zgr = zg[par, b, slot].cpu().numpy()
+                    diff = np.abs(zgr.astype(np.float64) - zo)
+                    st["max_logit_abs"] = max(st["max_logit_abs"], float(diff.max()))
+                    if w.d == 0:
+                        assert np.array_equal(zgr, zo), "supplied logits must be stored bit-exactly"
+                    else:
+                        scale = np.maximum(np.abs(zo), float(np.sqrt(np.mean(zo.astype(np.float64) ** 2))))
+                        rel = float((diff / scale).max())
+                        st["max_logit_rel"] = max(st["max_logit_rel"], rel)
+                        assert rel <= 2e-3, f"logit relative error {rel}"
+                        assert diff.max() <= 50 * self.logit_tol, f"logit abs error {diff.max()}"
+                amb = row["ambiguous"]
+                if len(amb):
+                    st["flag_topk"] += 1
+                    amb_rows.append((b, s))
+                    zamb = zg[par, b, slot][torch.from_numpy(amb).to(self.device)].cpu().numpy()
+                    gmem = zamb >= g["thr"][par, b, slot]
+                    omem = zo[amb] >= row["thr"]
+                    if not np.array_equal(gmem, omem):
+                        keep_override[(b, i_b[b] + s)] = {int(vv): bool(m) for vv, m in zip(amb, gmem)}
+        if keep_override:
+            st["adopt_topk"] += len(keep_override)
+            plan = o.evaluate(z_rows, keep_override)
+        for b in range(Bn):
+            par = t_b[b] & 1
+            for s in range(lives[b]):
+                slot = (i_b[b] + s) % L
+                row = plan[b][s]
+                assert g["nkept"][par, b, slot] == row["nkept"], \
+                    f"kept-set size b={b} s={s}: gpu {g['nkept'][par, b, slot]} oracle {row['nkept']}"
+                thr_g, thr_o = g["thr"][par, b, slot], row["thr"]
+                if w.d == 0 or not np.isfinite(thr_o):
+                    assert thr_g == thr_o, f"threshold differs: {thr_g} vs {thr_o}"
+                else:
+                    assert abs(float(thr_g) - float(thr_o)) <= 50 * self.logit_tol
+                dl = abs(float(g["lse"][par, b, slot]) - row["lse"])
+                st["max_lse_abs"] = max(st["max_lse_abs"], dl)
+                assert dl <= self.lse_tol * max(1.0, abs(row["lse"])), f"lse differs by {dl}"
+
+        # ---- one MRS per window position -----------------------------------
+        res = o.sample(plan)
+        acc_ov, res_ov = {}, {}
+        gk = g["k"].reshape(Bn, L)
+        gy = g["y"].reshape(Bn, L)
+        gpx = g["px"].reshape(Bn, L)
+        gqx = g["qx"].reshape(Bn, L)
+        for b in range(Bn):
+            for s in range(lives[b]):
+                r = res[b][s]
+                key = (b, i_b[b] + s)
+                st["draws"] += 1
+                st["flag_accept"] += r["flag_accept"]
+                st["flag_resid"] += r["flag_resid"]
+                for gval, oval in ((gpx[b, s], r["px"]), (gqx[b, s], r["qx"])):
+                    err = abs(float(gval) - oval)
+                    rel = err / max(oval, 1e-30) if oval > 0 else (0.0 if gval == 0 else np.inf)
+                    if oval > 1e-30:
+                        st["max_prob_rel"] = max(st["max_prob_rel"], rel)
+                    assert rel <= self.prob_rtol or err <= 1e-12 or key in keep_override, \
+                        f"p(x)/q(x) differs: gpu {gval} oracle {oval}"
+                if int(gk[b, s]) != r["k"]:
+                    assert r["flag_accept"], \
+                        f"accept bit differs on an unflagged draw b={b} s={s}: u={r['u']} px={r['px']} qx={r['qx']}"
+                    acc_ov[key] = int(gk[b, s])
+                elif r["k"] == 0 and int(gy[b, s]) != r["y"]:
+                    assert r["flag_resid"], f"residual token differs on an unflagged draw b={b} s={s}"
+                    res_ov[key] = int(gy[b, s])
+        if acc_ov or res_ov:
+            st["adopt_accept"] += len(acc_ov)
+            res = o.sample(plan, acc_ov, res_ov)
+            for (b, j), kk in acc_ov.items():     # a forced rejection resamples: token may be flagged too
+                s = j - i_b[b]
+                if kk == 0 and res[b][s]["y"] != int(gy[b, s]):
+                    assert res[b][s]["flag_resid"]
+                    res_ov[(b, j)] = int(gy[b, s])
+            st["adopt_resid"] += len(res_ov)
+            if res_ov:
+                res = o.sample(plan, acc_ov, res_ov)
+        for b in range(Bn):
+            for s in range(L):
+                if s < lives[b]:
+                    assert int(gk[b, s]) == res[b][s]["k"] and int(gy[b, s]) == res[b][s]["y"]
+                else:
+                    assert int(gk[b, s]) == 1 and int(gy[b, s]) == -1
+
+        # ---- commit --------------------------------------------------------
+        acc = o.commit(plan, res)
+        assert list(g["acc"]) == acc, f"accept lengths differ: {list(g['acc'])} vs {acc}"
+        assert list(g["pos"]) == list(o.i) and list(g["iter"]) == list(o.t)
+        assert int(g["verified"].sum()) == o.positions_verified
+        gX = g["X"].reshape(Bn, L)
+        gage = g["age"].reshape(Bn, L)
+        for b in range(Bn):
+            i, Lw = o.window(b)
+            for s in range(Lw):
+                slot = (i + s) % L
+                assert gX[b, slot] == o.X[b, i + s], "draft token differs after the slide"
+                assert gage[b, slot] == o.age[b, i + s], "age differs after the slide"
+        st["steps"] += 1
+        return acc
+
+    def run(self, max_steps=None):
+        while not self.oracle.done() and (max_steps is None or self.stats["steps"] < max_steps):
+            self.step()
+        out_g = self.v["out"].cpu().numpy().reshape(self.w.B, self.w.N)
+        assert np.array_equal(out_g, self.oracle.out), "emitted tokens differ"
+        if self.oracle.done():
+            rc, flags = self.gpu.status(self.state)
+            assert flags[1] == 1 and flags[2] == max(self.oracle.t)
+        return self.stats

@@ -1,0 +1,298 @@
+"""GPU parity tests: the HIP path, called through the C ABI, against the CPU
+oracle on the same seeded inputs.  Stage tests first (LM head, select/softmax,
+MRS, verify), then lock-step decodes of the five workloads (small ones whole,
+large ones a prefix of iterations in the benchmark's launch configuration),
+then edge cases."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import logits as lg
+from oracle import mrs as omrs
+from oracle import philox
+from paper_2510_24211_amd import binding as B
+from paper_2510_24211_amd import workload as wl
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def _bf16(bits):
+    return torch.from_numpy(bits.view(np.int16)).to(DEV).view(torch.bfloat16)
+
+
+@pytest.fixture(scope="module", autouse=True)
+def _require_gpu_and_library():
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    B.load()
+
+
+# ---------------------------------------------------------------- LM head
+@pytest.mark.parametrize("Bn,L,d,V,v_lo,v_hi,lam,tau", [
+    (1, 32, 256, 1024, 0, 1024, 0.0, 1.0),      # one tile column set, no CFG
+    (1, 32, 1280, 2000, 0, 2000, 0.0, 1.0),     # ragged vocabulary tail (2000 = 15*128 + 80)
+    (1, 32, 512, 4096, 4, 1300, 3.0, 1.0),      # CFG + unaligned id range
+    (2, 64, 520, 777, 0, 777, 3.0, 0.7),        # d not a multiple of the k tile, tau != 1
+    (3, 8, 64, 300, 10, 290, 3.0, 1.0),         # window shorter than a row block
+    (5, 40, 128, 640, 0, 640, 1.5, 1.0),        # L not a multiple of 32, odd B
+    (1, 1, 64, 256, 0, 256, 0.0, 1.0),          # L = 1
+    (16, 32, 256, 512, 0, 512, 3.0, 1.0),       # several row-block tiles share a W slab
+])
+def test_lm_head_against_oracle(Bn, L, d, V, v_lo, v_hi, lam, tau):
+    g = np.random.default_rng(hash((Bn, L, d, V)) % 2 ** 32)
+    C = 2 if lam else 1
+    h = wl.f32_to_bf16_bits(g.standard_normal((Bn, C, L, d)).astype(np.float32))
+    W = wl.f32_to_bf16_bits((g.standard_normal((V, d)) * 0.05).astype(np.float32))
+    cfg = B.make_config(B=Bn, L=L, N=10 * L, V=V, d=d, v_lo=v_lo, v_hi=v_hi, cfg_lambda=lam,
+                        temperature=tau)
+    s = B.Scd(cfg, DEV)
+    n = v_hi - v_lo
+    z = torch.full((Bn, L, n), float("nan"), device=DEV)
+    s.lm_head(_bf16(h), _bf16(W), z)
+    torch.cuda.synchronize()
+    zg = z.cpu().numpy()
+    W64 = lg.bf16_bits_to_f64(W[v_lo:v_hi])
+    for b in range(Bn):
+        c = lg.lm_head(h[b, 0], W64)
+        u = lg.lm_head(h[b, 1], W64) if C == 2 else None
+        zo = lg.process_logits(c, u, lam, tau)
+        diff = np.abs(zg[b].astype(np.float64) - zo)
+        scale = np.maximum(np.abs(zo), np.sqrt(np.mean(zo.astype(np.float64) ** 2)))
+        assert (diff / scale).max() <= 2e-3          # the stated bf16-GEMM bar
+        assert diff.max() <= 2e-5 * (1 + 2 * lam) * max(1.0, np.abs(zo).max())   # what fp32 accumulation gives
+
+
+# ------------------------------------------------------- select / softmax
+def _select_case(z, top_k):
+    rows, n = z.shape
+    cfg = B.make_config(B=1, L=1, N=1, V=n, top_k=top_k)
+    s = B.Scd(cfg, DEV)
+    thr = torch.empty(rows, device=DEV)
+    lse = torch.empty(rows, device=DEV)
+    nk = torch.empty(rows, dtype=torch.int32, device=DEV)
+    s.select(torch.from_numpy(z).to(DEV), rows, thr, lse, nk)
+    torch.cuda.synchronize()
+    thr, lse, nk = thr.cpu().numpy(), lse.cpu().numpy(), nk.cpu().numpy()
+    for r in range(rows):
+        p, thr_o, lse_o = lg.distribution(z[r], top_k)
+        assert thr[r] == thr_o, (r, thr[r], thr_o)                   # exact order statistic
+        assert nk[r] == int((p > 0).sum()) or nk[r] == int((z[r] >= thr_o).sum())
+        assert abs(float(lse[r]) - lse_o) <= 1e-6 * max(1.0, abs(lse_o))
+        # probabilities of the kept ids from the GPU's (thr, lse) against the oracle's softmax
+        keep = z[r] >= thr[r]
+        pg = np.where(keep, np.exp(z[r].astype(np.float64) - float(lse[r])), 0.0)
+        assert np.abs(pg - p).max() <= 1e-6
+
+
+@pytest.mark.parametrize("n,top_k", [(1024, 0), (1024, 100), (1000, 1), (1000, 999), (1000, 1000),
+                                     (1000, 5000), (8192, 2000), (65536, 2000), (16384, 1000),
+                                     (64000, 2000), (5, 2), (1, 1), (4097, 33)])
+def test_select_softmax_against_oracle(n, top_k):
+    g = np.random.default_rng(n * 31 + top_k)
+    z = (g.standard_normal((6, n)) * 3).astype(np.float32)
+    if n >= 1000:
+        z[1, g.integers(0, n, 50)] = -np.inf          # masked-out ids inside the row
+        z[2] = np.round(z[2] * 4) / 4                 # heavy ties, also at the threshold
+        z[3] = -np.abs(z[3]) - 100                    # all negative, large magnitude
+        z[4, :] = z[4, 0]                             # constant row
+    _select_case(z, top_k)
+
+
+# ------------------------------------------------------------- MRS stage
+@pytest.mark.parametrize("Bn,L,n,top_k,N,pos0", [
+    (1, 8, 1024, 0, 64, [0]),
+    (2, 16, 1000, 100, 40, [3, 30]),      # ragged n (scalar loads), second window clipped to 10 rows
+    (1, 32, 8192, 2000, 2304, [100]),
+    (3, 5, 37, 7, 50, [0, 45, 49]),       # tiny vocabulary, windows of 5 / 5 / 1 rows
+])
+def test_couple_draft_and_verify_against_oracle(Bn, L, n, top_k, N, pos0):
+    g = np.random.default_rng(n + L)
+    seed, it = 0xABCDEF0123456789, 7
+    base = (g.standard_normal((Bn, L, n)) * 2).astype(np.float32)
+    scale = np.float32(0.5) ** g.integers(0, 12, (Bn, L, 1)).astype(np.float32)
+    z_prev = base
+    z_cur = (base + scale * g.standard_normal((Bn, L, n)).astype(np.float32)).astype(np.float32)
+    z_cur[:, -1] = z_prev[:, -1]                         # identical rows: must accept
+    fresh = (g.random((Bn, L)) < 0.25).astype(np.uint8)
+    fresh[:, -1] = 0
+    # drafts: x ~ q
+    x = np.zeros((Bn, L), dtype=np.int32)
+    for b in range(Bn):
+        for s in range(L):
+            if fresh[b, s]:
+                x[b, s] = g.integers(0, n)
+            else:
+                q, _, _ = lg.distribution(z_prev[b, s], top_k)
+                x[b, s] = g.choice(n, p=q)
+    cfg = B.make_config(B=Bn, L=L, N=N, V=n, top_k=top_k, seed=seed)
+    sc = B.Scd(cfg, DEV)
+    t = lambda a: torch.from_numpy(a).to(DEV)
+    y = torch.empty((Bn, L), dtype=torch.int32, device=DEV)
+    k = torch.empty((Bn, L), dtype=torch.uint8, device=DEV)
+    pos_t = t(np.array(pos0, dtype=np.int32))
+    sc.couple_draft(t(z_cur), t(z_prev), t(x), t(fresh), pos_t, it, y, k)
+    acc = torch.empty(Bn, dtype=torch.int32, device=DEV)
+    out = torch.full((Bn, N), -7, dtype=torch.int32, device=DEV)
+    sc.verify(k, y, pos_t, acc, out)
+    torch.cuda.synchronize()
+    y, k, acc, out = y.cpu().numpy(), k.cpu().numpy(), acc.cpu().numpy(), out.cpu().numpy()
+    n_rej = 0
+    for b in range(Bn):
+        live = min(L, N - pos0[b])
+        first = live
+        for s in range(L):
+            if s >= live:
+                assert y[b, s] == -1 and k[b, s] == 1
+                continue
+            j = pos0[b] + s
+            p, _, _ = lg.distribution(z_cur[b, s], top_k)
+            q = np.full(n, np.float64(np.float32(1.0) / np.float32(n))) if fresh[b, s] \
+                else lg.distribution(z_prev[b, s], top_k)[0]
+            u = philox.uniform_scalar(seed, b, j, it, philox.STREAM_ACCEPT)
+            r = omrs.mrs(p, q, int(x[b, s]), u,
+                         lambda: philox.uniform_per_vocab(seed, b, j, it, philox.STREAM_RESID, n))
+            if k[b, s] != r["k"]:
+                assert r["flag_accept"], (b, s)
+            elif r["k"] == 0 and y[b, s] != r["y"]:
+                assert r["flag_resid"], (b, s)
+            else:
+                assert y[b, s] == r["y"]
+            n_rej += 1 - int(k[b, s])
+            if k[b, s] == 0 and first == live:
+                first = s
+        a = min(first + 1, live)
+        assert acc[b] == a
+        assert np.array_equal(out[b, pos0[b]:pos0[b] + a], y[b, :a])       # v_lo = 0
+        assert (out[b, :pos0[b]] == -7).all() and (out[b, pos0[b] + a:] == -7).all()
+    assert (k[:, -1] == 1).all() or any(min(L, N - p) < L for p in pos0)    # identical rows accepted
+    assert n_rej > 0                                                         # the race was exercised
+
+
+# ------------------------------------------------------ lock-step decodes
+def _lockstep(w, max_steps=None, **kw):
+    from lockstep import LockStep
+    ls = LockStep(w, DEV, **kw)
+    st = ls.run(max_steps)
+    print(f"\n[{w.name}] {st}")
+    # flagged draws are rare; adopted ones rarer
+    assert st["adopt_accept"] + st["adopt_resid"] <= max(3, 1e-3 * st["draws"])
+    return ls, st
+
+
+def test_lockstep_C0_full_and_golden():
+    import json, os
+    ls, st = _lockstep(wl.WORKLOADS["C0"])
+    want = json.load(open(os.path.join(os.path.dirname(__file__), "golden", "c0_golden.json")))
+    assert [int(x) for x in ls.oracle.out[0]] == want["tokens"]
+    assert ls.oracle.t[0] == want["nfe"] and ls.oracle.accept_hist[0] == want["accept_len"]
+    assert st["adopt_accept"] == st["adopt_resid"] == st["adopt_topk"] == 0
+
+
+@pytest.mark.parametrize("kw", [
+    dict(N=40, L=8, seed=11),
+    dict(N=33, L=1, seed=12),                       # plain autoregressive sampling
+    dict(N=5, L=8, seed=13),                        # sequence shorter than the window
+    dict(N=50, L=16, seed=14, top_k=64),
+    dict(N=70, L=8, seed=15, B=3, V=1000),          # batch, ragged n
+    dict(N=64, L=64, seed=16, top_k=10, V=300),
+    dict(N=300, L=128, seed=17, V=512),             # window longer than a wavefront
+])
+def test_lockstep_toy_variants(kw):
+    _lockstep(wl.scaled(wl.WORKLOADS["C0"], name="toy", **kw))
+
+
+@pytest.mark.parametrize("kw", [
+    dict(name="C1s", N=96, V=2048, d=256, top_k=200),
+    dict(name="C1r", N=50, V=1000, d=72, top_k=100, L=8, B=2),      # ragged everything
+])
+def test_lockstep_scaled_lm_head(kw):
+    _lockstep(wl.scaled(wl.WORKLOADS["C1"], **kw))
+
+
+def test_lockstep_scaled_cfg_masked_batched():
+    # C3-like: CFG, unaligned allowed range, 4 sequences that finish at different iterations
+    _lockstep(wl.scaled(wl.WORKLOADS["C3"], name="C3s", B=4, N=80, V=4096, d=256, v_lo=4, v_hi=1028,
+                        top_k=250))
+
+
+def test_lockstep_scaled_video():
+    _lockstep(wl.scaled(wl.WORKLOADS["C4"], name="C4s", N=8 * 24, V=2000, d=512, top_k=300, L=64))
+
+
+def test_lockstep_C1_full():
+    _lockstep(wl.WORKLOADS["C1"], check_logits=False)
+
+
+def test_lockstep_C2_prefix():
+    _lockstep(wl.WORKLOADS["C2"], max_steps=40)
+
+
+def test_lockstep_C2_fullV_prefix():
+    _lockstep(wl.WORKLOADS["C2-fullV"], max_steps=5)
+
+
+def test_lockstep_C3_prefix():
+    _lockstep(wl.WORKLOADS["C3"], max_steps=4)
+
+
+def test_lockstep_C4_prefix():
+    _lockstep(wl.WORKLOADS["C4"], max_steps=3)
+
+
+# --------------------------------------------------------------- edge cases
+def test_determinism_and_finished_sequences_untouched():
+    w = wl.scaled(wl.WORKLOADS["C1"], name="det", N=64, V=1024, d=128, top_k=100, B=2)
+    cfg = B.config_from_workload(w)
+    W = _bf16(wl.lm_head_weight(w))
+    tab = wl.HiddenTable(w)
+    table = _bf16(tab.full())
+    outs = []
+    for rep in range(2):
+        s = B.Scd(cfg, DEV)
+        st = s.alloc_state()
+        s.reset(st)
+        h = torch.empty((w.B, w.C, w.L, w.d), dtype=torch.bfloat16, device=DEV)
+        for _ in range(w.N + 5):                   # more steps than any decode needs
+            s.gather_hidden(table, w.age_cap, st, h)
+            s.step(h, W, st)
+        rc, flags = s.status(st)
+        assert rc == B.SCD_OK and flags[1] == 1
+        outs.append((s.state_field(st, B.F_OUT).cpu().numpy().copy(),
+                     s.state_field(st, B.F_ITER).cpu().numpy().copy(),
+                     s.state_field(st, B.F_POS).cpu().numpy().copy()))
+    assert np.array_equal(outs[0][0], outs[1][0]) and np.array_equal(outs[0][1], outs[1][1])
+    assert (outs[0][0] >= 0).all() and (outs[0][2] == w.N).all()
+    assert (outs[0][1] < w.N).all()               # extra steps after the end did not count
+
+
+def test_gather_matches_host_gather():
+    w = wl.scaled(wl.WORKLOADS["C2"], name="g", N=70, V=512, d=64, v_lo=0, v_hi=512, B=2)
+    cfg = B.config_from_workload(w)
+    s = B.Scd(cfg, DEV)
+    st = s.alloc_state()
+    s.reset(st)
+    tab = wl.HiddenTable(w)
+    table = _bf16(tab.full(drop_cache=False))
+    pos = np.array([3, 60], dtype=np.int32)
+    age = np.random.default_rng(0).integers(0, 30, (w.B, w.L)).astype(np.int32)
+    s.state_field(st, B.F_POS).copy_(torch.from_numpy(pos))
+    s.state_field(st, B.F_AGE).copy_(torch.from_numpy(age.ravel()))
+    h = torch.empty((w.B, w.C, w.L, w.d), dtype=torch.bfloat16, device=DEV)
+    s.gather_hidden(table, w.age_cap, st, h)
+    torch.cuda.synchronize()
+    ages = [[age[b, (pos[b] + k) % w.L] for k in range(w.L)] for b in range(w.B)]
+    want = tab.window(list(pos), ages)
+    assert np.array_equal(h.view(torch.int16).cpu().numpy().view(np.uint16), want)
+
+
+def test_numeric_fault_is_reported():
+    w = wl.scaled(wl.WORKLOADS["C0"], name="nan", N=16, L=4, V=256)
+    cfg = B.config_from_workload(w)
+    s = B.Scd(cfg, DEV)
+    st = s.alloc_state()
+    s.reset(st)
+    z = torch.zeros((1, 4, 256), device=DEV)
+    z[0, 1, 5] = float("nan")
+    s.step_logits(z, st)
+    rc, flags = s.status(st)
+    assert rc == B.SCD_ENUMERIC and flags[0] != 0

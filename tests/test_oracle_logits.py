@@ -74,7 +74,7 @@ def test_softmax_without_topk_is_library_softmax():
     np.testing.assert_allclose(lse, special.logsumexp(z.astype(np.float64)), rtol=1e-14)
     # K = |A| keeps everything as well
     p2, thr2, _ = lg.distribution(z, z.size)
-    assert thr2 == z.min()
+    assert thr2 == -np.inf
     np.testing.assert_allclose(p2, p, rtol=1e-13)
 
 
@@ -97,7 +97,8 @@ def test_topk_brute_force_and_ties():
     p, _ = lg.softmax_kept(z, thr)
     assert (p > 0).sum() == 4
     # K larger than the row
-    assert lg.topk_threshold(z, 100) == 0.0
+    assert lg.topk_threshold(z, 100) == -np.inf and lg.topk_threshold(z, 6) == -np.inf
+    assert lg.topk_threshold(z, 5) == 1.0
 
 
 def test_lse_consistency():
