@@ -60,11 +60,14 @@ class ScdConfig:
 
 def _ambiguous_ids(z, thr, top_k, tol_z):
     """Ids whose membership in the top-k set could flip under a logit
-    perturbation of tol_z: strictly different from thr but within tol_z."""
+    perturbation of tol_z: every id within tol_z of the threshold, the K-th
+    itself included (an exact tie here may be split elsewhere), provided there
+    is more than one such id."""
     if top_k <= 0 or top_k >= z.shape[-1]:
         return np.zeros(0, dtype=np.int64)
     d = np.abs(z.astype(np.float64) - np.float64(thr))
-    return np.nonzero((d > 0) & (d <= tol_z))[0]
+    ids = np.nonzero(d <= tol_z)[0]
+    return ids if ids.size > 1 else np.zeros(0, dtype=np.int64)
 
 
 class ScdOracle:

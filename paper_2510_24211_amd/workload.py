@@ -84,7 +84,10 @@ WORKLOADS = {
 
 
 def scaled(w: Workload, **kw) -> Workload:
-    """A smaller or otherwise modified copy of a workload (tests)."""
+    """A smaller or otherwise modified copy of a workload (tests).  An id range
+    that covered the whole vocabulary keeps covering it when V changes."""
+    if "V" in kw and "v_hi" not in kw and w.v_lo == 0 and w.v_hi == w.V:
+        kw["v_hi"] = kw["V"]
     return replace(w, **kw)
 
 
