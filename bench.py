@@ -1,0 +1,251 @@
+#!/usr/bin/env python3
+"""Benchmark of the SCD draft-and-verify step on one MI355X.
+
+A "step" is one whole decode iteration (scd_step: LM-head GEMM + CFG +
+temperature, top-k select + softmax normaliser, vectorised MRS, first
+rejection / emit / window slide) over the synthetic workload's current Jacobi
+windows, plus the device-side gather that assembles the windows' hidden states
+from the pre-generated table (all inputs are resident in HBM before the timed
+region starts; nothing crosses PCIe inside it).
+
+Prints ONE JSON line.  `value` = window positions verified per second over the
+timed steps; `tokens_per_s` = emitted tokens per second over the same steps.
+`roofline` describes the dominant kernel (the LM-head stream over W), timed with
+HIP events recorded inside scd_step on the stream it runs on.  `cpu_baseline`
+is the NumPy oracle timed on the host cores on a bounded sample of the same
+workload.
+"""
+import argparse
+import ctypes
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=0, help="timed steps; 0 = one whole decode")
+    ap.add_argument("--warmup", type=int, default=0, help="untimed steps; 0 = one whole decode")
+    ap.add_argument("--workload", default="C2",
+                    help="C1 | C2 | C2-fullV | C3 | C4 (see paper_2510_24211_amd/workload.py)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-seconds", type=float, default=15.0)
+    ap.add_argument("--no-events", action="store_true",
+                    help="do not record the per-step LM-head events (roofline from a second pass)")
+    return ap.parse_args()
+
+
+class HipEvents:
+    """hipEvent_t pairs created through the HIP runtime (ctypes)."""
+
+    def __init__(self, n):
+        self.hip = ctypes.CDLL("libamdhip64.so")
+        self.hip.hipEventCreate.argtypes = [ctypes.POINTER(ctypes.c_void_p)]
+        self.hip.hipEventElapsedTime.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.c_void_p,
+                                                 ctypes.c_void_p]
+        self.hip.hipEventDestroy.argtypes = [ctypes.c_void_p]
+        self.ev = []
+        for _ in range(2 * n):
+            e = ctypes.c_void_p()
+            assert self.hip.hipEventCreate(ctypes.byref(e)) == 0
+            self.ev.append(e)
+
+    def pair(self, i):
+        return self.ev[2 * i].value, self.ev[2 * i + 1].value
+
+    def elapsed_ms(self, i):
+        ms = ctypes.c_float()
+        rc = self.hip.hipEventElapsedTime(ctypes.byref(ms), self.ev[2 * i], self.ev[2 * i + 1])
+        assert rc == 0, rc
+        return ms.value
+
+    def destroy(self):
+        for e in self.ev:
+            self.hip.hipEventDestroy(e)
+
+
+def cpu_baseline(w, seconds):
+    """The oracle as it stands, on the host cores, for about `seconds`."""
+    import numpy as np
+    from oracle import logits as lg
+    from oracle import scd as oscd
+    from paper_2510_24211_amd import workload as wl
+    try:
+        from threadpoolctl import threadpool_info
+        threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        threads = os.cpu_count()
+    W = wl.lm_head_weight(w)
+    W64 = lg.bf16_bits_to_f64(W[w.v_lo:w.v_hi])
+    del W
+    tab = wl.HiddenTable(w)
+    o = oscd.ScdOracle(oscd.ScdConfig(B=w.B, L=w.L, N=w.N, V=w.V, v_lo=w.v_lo, v_hi=w.v_hi,
+                                      top_k=w.top_k, temperature=w.temperature,
+                                      cfg_lambda=w.cfg_lambda, seed=w.seed))
+    # inputs of the first windows are generated before the clock starts
+    tab.window(list(o.i), [[0] * w.L for _ in range(w.B)])
+    t_in = 0.0
+    t0 = time.perf_counter()
+    steps = 0
+    while not o.done() and time.perf_counter() - t0 - t_in < seconds:
+        ti = time.perf_counter()
+        ages = [[int(o.age[b, o.i[b] + s]) if o.i[b] + s < w.N else 0 for s in range(w.L)]
+                for b in range(w.B)]
+        h = tab.window(list(o.i), ages)
+        t_in += time.perf_counter() - ti          # input generation is not the method
+        z_rows = []
+        for b in range(w.B):
+            Lw = o.window(b)[1]
+            if Lw == 0:
+                z_rows.append(None)
+                continue
+            c = lg.lm_head(h[b, 0, :Lw], W64)
+            u = lg.lm_head(h[b, 1, :Lw], W64) if w.C == 2 else None
+            z_rows.append(lg.process_logits(c, u, w.cfg_lambda, w.temperature))
+        o.step(z_rows)
+        steps += 1
+    T = time.perf_counter() - t0 - t_in
+    return {"value": o.positions_verified / T, "unit": "positions/s", "cores": int(threads),
+            "kind": "oracle", "tokens_per_s": float(sum(o.i)) / T,
+            "sample": f"first {steps} iterations of {w.name} ({o.positions_verified} window "
+                      f"positions, {sum(o.i)} tokens) in {T:.1f} s, NumPy fp64"}
+
+
+def main():
+    a = parse()
+    if a.gpus != 1:
+        print("bench.py: this build measures ONE MI355X; --gpus must be 1 "
+              "(no multi-GPU path exists in this repository)", file=sys.stderr)
+        sys.exit(2)
+    import numpy as np
+    import torch
+    from paper_2510_24211_amd import binding as B
+    from paper_2510_24211_amd import workload as wl
+
+    w = wl.WORKLOADS[a.workload]
+    assert w.d > 0, "the benchmark runs the LM-head path"
+    dev = "cuda:0"
+    assert torch.cuda.is_available(), "bench.py needs the GPU (there is no CPU fallback)"
+    torch.cuda.set_device(0)
+
+    to_dev = lambda bits: torch.from_numpy(bits.view(np.int16)).to(dev).view(torch.bfloat16)
+    t_setup = time.perf_counter()
+    W = to_dev(wl.lm_head_weight(w))
+    table = to_dev(wl.HiddenTable(w).full())
+    s = B.Scd(B.config_from_workload(w), dev)
+    st = s.alloc_state()
+    h = torch.empty((w.B, w.C, w.L, w.d), dtype=torch.bfloat16, device=dev)
+    t_setup = time.perf_counter() - t_setup
+
+    def run_steps(k):
+        for _ in range(k):
+            s.gather_hidden(table, w.age_cap, st, h)
+            s.step(h, W, st)
+
+    def decode_to_end():
+        """Untimed whole decode; returns its iteration count (deterministic)."""
+        s.reset(st)
+        while True:
+            run_steps(16)
+            rc, flags = s.status(st)
+            assert rc == B.SCD_OK, (rc, flags)
+            if flags[1]:
+                return flags[2]
+
+    nfe = decode_to_end()                         # also the warm-up when --warmup 0
+    verified_per_decode = int(s.state_field(st, B.F_VERIFIED).sum().item())
+    K = a.steps if a.steps > 0 else nfe
+    Wm = a.warmup
+    s.reset(st)
+    if Wm > 0:
+        run_steps(min(Wm, nfe))
+        s.reset(st)
+
+    use_events = not a.no_events
+    ev = HipEvents(K) if use_events else None
+
+    def timed_pass(with_events):
+        s.reset(st)
+        torch.cuda.synchronize()
+        done_decodes, in_decode = 0, 0
+        t0 = time.perf_counter()
+        for i in range(K):
+            if in_decode == nfe:                  # sequence(s) finished: start the next decode
+                s.reset(st)
+                done_decodes, in_decode = done_decodes + 1, 0
+            if with_events:
+                s.set_lm_head_events(*ev.pair(i))
+            s.gather_hidden(table, w.age_cap, st, h)
+            s.step(h, W, st)
+            in_decode += 1
+        torch.cuda.synchronize()
+        T = time.perf_counter() - t0
+        if with_events:
+            s.set_lm_head_events(None, None)
+        verified = done_decodes * verified_per_decode + int(s.state_field(st, B.F_VERIFIED).sum().item())
+        tokens = done_decodes * w.B * w.N + int(s.state_field(st, B.F_POS).sum().item())
+        return T, verified, tokens
+
+    T, verified, tokens = timed_pass(use_events)
+    rc, flags = s.status(st)
+    assert rc == B.SCD_OK
+
+    lm_ms = None
+    if use_events:
+        lm_ms = float(np.mean([ev.elapsed_ms(i) for i in range(K)]))
+        ev.destroy()
+
+    n = w.n_allowed
+    w_bytes = 2 * w.d * n
+    h_bytes = 2 * w.M * w.d
+    alg_bytes = w_bytes + h_bytes               # per LM-head launch (W slice once + hidden rows)
+    flops = 2.0 * w.M * w.d * n
+    roof = None
+    if lm_ms:
+        gbs = alg_bytes / (lm_ms * 1e-3) / 1e9
+        traffic = None
+        tpath = os.path.join(ROOT, "profiles", f"traffic_{w.name}.json")
+        if os.path.exists(tpath):
+            traffic = json.load(open(tpath)).get("hbm_bytes_per_launch")
+        roof = {"bound": "hbm", "achieved": gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": gbs / HBM_PEAK_GBS, "traffic": traffic, "kernel": "lm_head_kernel",
+                "avg_launch_us": lm_ms * 1e3, "algorithmic_bytes_per_launch": alg_bytes,
+                "mfma_tflops": flops / (lm_ms * 1e-3) / 1e12,
+                "mfma_frac": flops / (lm_ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS}
+
+    out = {
+        "metric": "window_positions_verified_per_s",
+        "value": verified / T,
+        "unit": "positions/s",
+        "tokens_per_s": tokens / T,
+        "n_gpus": 1, "steps": K, "warmup": Wm if Wm > 0 else nfe,
+        "ms_per_step": T / K * 1e3,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"{w.name}: B={w.B} CFG={'on' if w.C == 2 else 'off'} L={w.L} "
+                               f"N={w.N} V={w.V} allowed={n} d={w.d} top_k={w.top_k} "
+                               f"lambda={w.cfg_lambda} seed={w.seed} (synthetic drift model)",
+                   "decode_iterations": int(nfe), "tokens_per_iteration": w.B * w.N / nfe,
+                   "step_bytes_algorithmic": alg_bytes + 2 * w.B * w.L * min(n, w.top_k or n) * 8,
+                   "step_hbm_frac": (alg_bytes + 2 * w.B * w.L * min(n, w.top_k or n) * 8)
+                   / (T / K) / 1e9 / HBM_PEAK_GBS,
+                   "lm_head_events_in_timed_region": bool(use_events),
+                   "setup_s": t_setup},
+        "roofline": roof,
+    }
+    if not a.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(w, a.cpu_seconds)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -161,6 +161,12 @@ int scd_verify(scd_ctx* ctx, const uint8_t* d_k, const int32_t* d_y, const int32
  * Finished sequences cost nothing and change nothing.  Requires cfg.d > 0. */
 int scd_step(scd_ctx* ctx, const uint16_t* d_h, const uint16_t* d_W, void* d_state);
 
+/* Optional instrumentation for benchmarks: while both events are non-NULL,
+ * scd_step records ev_start immediately before and ev_stop immediately after
+ * the LM-head kernel on the context's stream (hipEvent_t passed as void*, owned
+ * by the caller).  NULL, NULL turns it off.  Host-only call. */
+int scd_set_lm_head_events(scd_ctx* ctx, void* ev_start, void* ev_stop);
+
 /* The same iteration with the processed logits supplied by the caller
  * (d_z fp32 [B, L, n], window order) instead of computed by the LM head. */
 int scd_step_logits(scd_ctx* ctx, const float* d_z, void* d_state);

@@ -70,12 +70,14 @@ def load():
     lib.scd_verify.argtypes = [vp, vp, vp, vp, vp, vp]
     lib.scd_step.argtypes = [vp, vp, vp, vp]
     lib.scd_step_logits.argtypes = [vp, vp, vp]
+    lib.scd_set_lm_head_events.argtypes = [vp, vp, vp]
     lib.scd_status.argtypes = [vp, vp, ctypes.POINTER(i32 * 4)]
     lib.scd_strerror.restype = ctypes.c_char_p
     lib.scd_strerror.argtypes = [ctypes.c_int]
     lib.scdw_gather_hidden.argtypes = [vp, vp, i32, i32, i32, i32, i32, i32, vp, vp, vp]
     for name in ("scd_create", "scd_destroy", "scd_reset", "scd_state_field", "scd_lm_head",
                  "scd_select", "scd_couple_draft", "scd_verify", "scd_step", "scd_step_logits",
+                 "scd_set_lm_head_events",
                  "scd_status", "scdw_gather_hidden"):
         getattr(lib, name).restype = ctypes.c_int
     _lib = lib
@@ -214,6 +216,12 @@ class Scd:
             self.ctx, _ptr(h, _BF16, c.B * self.C * c.L * c.d, "h"),
             _ptr(W, _BF16, c.V * c.d, "W"),
             _ptr(state, (torch.uint8,), state_bytes(c), "state")), "scd_step")
+
+    def set_lm_head_events(self, ev_start, ev_stop):
+        """ev_*: hipEvent_t handles as integers (or None, None to turn off)."""
+        self._check(self.lib.scd_set_lm_head_events(
+            self.ctx, ctypes.c_void_p(ev_start) if ev_start else None,
+            ctypes.c_void_p(ev_stop) if ev_stop else None), "scd_set_lm_head_events")
 
     def step_logits(self, z, state):
         c = self.cfg

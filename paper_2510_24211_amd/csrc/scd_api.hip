@@ -82,6 +82,7 @@ struct scd_ctx {
   hipStream_t stream;
   int n;   // allowed ids
   int C;   // LM-head rows per window position
+  hipEvent_t ev_start, ev_stop;   // optional instrumentation around the LM-head kernel
 };
 
 namespace {
@@ -169,6 +170,8 @@ int scd_create(scd_ctx** out, const scd_config* cfg, void* d_workspace, size_t w
   c->stream = static_cast<hipStream_t>(hip_stream);
   c->n = cfg->v_hi - cfg->v_lo;
   c->C = cfg->cfg_lambda != 0.f ? 2 : 1;
+  c->ev_start = nullptr;
+  c->ev_stop = nullptr;
   *out = c;
   return SCD_OK;
 }
@@ -279,8 +282,18 @@ int scd_step(scd_ctx* c, const uint16_t* d_h, const uint16_t* d_W, void* st) {
   a.lam = c->cfg.cfg_lambda;
   a.one_plus_lam = 1.0f + c->cfg.cfg_lambda;
   a.tau = c->cfg.temperature;
+  const bool timed = c->ev_start && c->ev_stop;
+  if (timed && hipEventRecord(c->ev_start, c->stream) != hipSuccess) return SCD_EHIP;
   if (hipError_t e = scd::launch_lm_head(a, c->stream); e != hipSuccess) return SCD_EHIP;
+  if (timed && hipEventRecord(c->ev_stop, c->stream) != hipSuccess) return SCD_EHIP;
   return run_tail(c, st);
+}
+
+int scd_set_lm_head_events(scd_ctx* c, void* ev_start, void* ev_stop) {
+  if (!c || ((ev_start == nullptr) != (ev_stop == nullptr))) return SCD_EINVAL;
+  c->ev_start = static_cast<hipEvent_t>(ev_start);
+  c->ev_stop = static_cast<hipEvent_t>(ev_stop);
+  return SCD_OK;
 }
 
 int scd_step_logits(scd_ctx* c, const float* d_z, void* st) {
