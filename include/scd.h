@@ -94,7 +94,8 @@ typedef enum scd_field {
   SCD_F_Z = 13,       /* float [2, B, L, n] processed logits per parity and slot       */
   SCD_F_FLAGS = 14,   /* int32 [4]       [0] numeric-fault bits                        */
   SCD_F_VERIFIED = 15,/* int32 [B]       window positions verified so far (sum of Lw)  */
-  SCD_F_COUNT = 16
+  SCD_F_TICKET = 16,  /* int32 [B]       internal arrival counters, zero between steps */
+  SCD_F_COUNT = 17
 } scd_field;
 
 /* Bytes of caller-provided device scratch a context needs; 0 on a bad config. */

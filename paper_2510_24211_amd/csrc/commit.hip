@@ -70,6 +70,7 @@ __global__ void reset_kernel(const ResetArgs a) {
     a.iter[t] = 0;
     a.accept_len[t] = 0;
     a.verified[t] = 0;
+    a.ticket[t] = 0;
   }
   if (gid < 4) a.flags[gid] = 0;
 }

@@ -54,6 +54,7 @@ Layout make_layout(const scd_config& c) {
   sz[SCD_F_Z] = 4 * 2 * B * L * n;
   sz[SCD_F_FLAGS] = 16;
   sz[SCD_F_VERIFIED] = 4 * B;
+  sz[SCD_F_TICKET] = 4 * B;
   Layout lay;
   size_t o = 0;
   for (int f = 0; f < SCD_F_COUNT; ++f) {
@@ -95,8 +96,38 @@ inline int hip_rc(hipError_t e) { return e == hipSuccess ? SCD_OK : SCD_EHIP; }
 inline bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
 
 int run_tail(scd_ctx* c, void* st) {
-  // select -> MRS -> commit on the ring state; z of this iteration is in place.
+  // z of this iteration is in place in the ring.
   const size_t half = static_cast<size_t>(c->cfg.B) * c->cfg.L * c->n;
+  if (c->n <= scd::kRowKernelMaxN) {
+    // one fused launch: select + softmax + MRS per row, commit by each sequence's last row
+    scd::RowArgs ra{};
+    ra.mode = scd::kRowRing;
+    ra.z_cur = field<float>(c, st, SCD_F_Z);
+    ra.parity_stride = half;
+    ra.thr = field<float>(c, st, SCD_F_THR);
+    ra.lse = field<float>(c, st, SCD_F_LSE);
+    ra.nkept = field<int32_t>(c, st, SCD_F_NKEPT);
+    ra.x = field<int32_t>(c, st, SCD_F_X);
+    ra.age = field<int32_t>(c, st, SCD_F_AGE);
+    ra.pos = field<int32_t>(c, st, SCD_F_POS);
+    ra.iter = field<int32_t>(c, st, SCD_F_ITER);
+    ra.y = field<int32_t>(c, st, SCD_F_Y);
+    ra.k = field<uint8_t>(c, st, SCD_F_K);
+    ra.px = field<float>(c, st, SCD_F_PX);
+    ra.qx = field<float>(c, st, SCD_F_QX);
+    ra.flags = field<int32_t>(c, st, SCD_F_FLAGS);
+    ra.ticket = field<int32_t>(c, st, SCD_F_TICKET);
+    ra.X = field<int32_t>(c, st, SCD_F_X);
+    ra.age_w = field<int32_t>(c, st, SCD_F_AGE);
+    ra.verified = field<int32_t>(c, st, SCD_F_VERIFIED);
+    ra.accept_len = field<int32_t>(c, st, SCD_F_ACCEPT);
+    ra.out = field<int32_t>(c, st, SCD_F_OUT);
+    ra.rows = c->cfg.B * c->cfg.L;
+    ra.B = c->cfg.B; ra.L = c->cfg.L; ra.N = c->cfg.N; ra.n = c->n; ra.top_k = c->cfg.top_k;
+    ra.v_lo = c->cfg.v_lo; ra.seed = c->cfg.seed;
+    return hip_rc(scd::launch_row(ra, c->stream));
+  }
+  // rows too long for the LDS-resident kernel: select -> MRS -> commit
   scd::SelectArgs sa{};
   sa.z = field<float>(c, st, SCD_F_Z);
   sa.parity_stride = half;
@@ -200,6 +231,7 @@ int scd_reset(scd_ctx* c, void* st) {
   a.accept_len = field<int32_t>(c, st, SCD_F_ACCEPT);
   a.verified = field<int32_t>(c, st, SCD_F_VERIFIED);
   a.flags = field<int32_t>(c, st, SCD_F_FLAGS);
+  a.ticket = field<int32_t>(c, st, SCD_F_TICKET);
   a.B = c->cfg.B; a.L = c->cfg.L; a.N = c->cfg.N; a.n = c->n; a.seed = c->cfg.seed;
   return hip_rc(scd::launch_reset(a, c->stream));
 }
@@ -222,6 +254,14 @@ int scd_lm_head(scd_ctx* c, const uint16_t* d_h, const uint16_t* d_W, float* d_z
 int scd_select(scd_ctx* c, const float* d_z, int32_t rows, float* d_thr, float* d_lse,
                int32_t* d_nkept) {
   if (!c || !d_z || rows < 0 || !d_thr || !d_lse || !d_nkept) return SCD_EINVAL;
+  if (c->n <= scd::kRowKernelMaxN) {
+    scd::RowArgs ra{};
+    ra.mode = scd::kRowSelectOnly;
+    ra.z_cur = d_z; ra.thr = d_thr; ra.lse = d_lse; ra.nkept = d_nkept;
+    ra.rows = rows;
+    ra.B = c->cfg.B; ra.L = c->cfg.L; ra.N = c->cfg.N; ra.n = c->n; ra.top_k = c->cfg.top_k;
+    return hip_rc(scd::launch_row(ra, c->stream));
+  }
   scd::SelectArgs a{};
   a.z = d_z; a.thr = d_thr; a.lse = d_lse; a.nkept = d_nkept;
   a.rows = rows;
@@ -243,8 +283,22 @@ int scd_couple_draft(scd_ctx* c, const float* d_z_cur, const float* d_z_prev, co
   float* thr_p = reinterpret_cast<float*>(w + 3 * seg);
   float* lse_p = reinterpret_cast<float*>(w + 4 * seg);
   int32_t* nk_p = reinterpret_cast<int32_t*>(w + 5 * seg);
-  if (int rc = scd_select(c, d_z_cur, rows, thr_c, lse_c, nk_c); rc != SCD_OK) return rc;
   if (int rc = scd_select(c, d_z_prev, rows, thr_p, lse_p, nk_p); rc != SCD_OK) return rc;
+  if (c->n <= scd::kRowKernelMaxN) {
+    scd::RowArgs ra{};
+    ra.mode = scd::kRowPlain;
+    ra.z_cur = d_z_cur; ra.z_prev = d_z_prev;
+    ra.thr = thr_c; ra.lse = lse_c; ra.nkept = nk_c;
+    ra.thr_prev = thr_p; ra.lse_prev = lse_p;
+    ra.x = d_x; ra.fresh = d_fresh; ra.pos = const_cast<int32_t*>(d_pos0);
+    ra.iter_scalar = iter;
+    ra.y = d_y; ra.k = d_k;
+    ra.rows = rows;
+    ra.B = c->cfg.B; ra.L = c->cfg.L; ra.N = c->cfg.N; ra.n = c->n; ra.top_k = c->cfg.top_k;
+    ra.v_lo = c->cfg.v_lo; ra.seed = c->cfg.seed;
+    return hip_rc(scd::launch_row(ra, c->stream));
+  }
+  if (int rc = scd_select(c, d_z_cur, rows, thr_c, lse_c, nk_c); rc != SCD_OK) return rc;
   scd::MrsArgs a{};
   a.z_cur = d_z_cur; a.z_prev = d_z_prev;
   a.thr_cur = thr_c; a.lse_cur = lse_c; a.thr_prev = thr_p; a.lse_prev = lse_p;

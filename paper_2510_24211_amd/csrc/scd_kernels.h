@@ -60,6 +60,44 @@ struct MrsArgs {
 };
 hipError_t launch_mrs(const MrsArgs& a, hipStream_t s);
 
+// ---- fused row kernel: select + softmax + MRS (+ commit by the last arriver) --
+enum { kRowSelectOnly = 0, kRowPlain = 1, kRowRing = 2 };
+constexpr int kRowKernelMaxN = 65536;   // the LDS copy of the key prefixes must fit
+struct RowArgs {
+  int mode;
+  const float* z_cur;    // select-only: [rows, n]; plain: [B, L, n]; ring: base of [2, B, L, n]
+  const float* z_prev;   // plain: [B, L, n]
+  size_t parity_stride;  // ring: floats between the halves of z
+  float* thr;            // select-only / plain: [rows]; ring: [2, B, L] (both parities)
+  float* lse;
+  int32_t* nkept;
+  const float* thr_prev; // plain: [B*L]
+  const float* lse_prev;
+  const int32_t* x;      // plain: [B, L] window order; ring: [B, L] by slot (also written)
+  const uint8_t* fresh;  // plain: [B, L] or null
+  const int32_t* age;    // ring: [B, L] by slot
+  int32_t* pos;          // [B]
+  int32_t* iter;         // ring: [B]
+  int iter_scalar;       // plain
+  int32_t* y;            // [B, L] window order
+  uint8_t* k;
+  float* px;             // [B, L] or null
+  float* qx;
+  int32_t* flags;        // numeric-fault bits or null
+  // ring mode: state updated by the last workgroup of each sequence
+  int32_t* ticket;       // [B], zero between launches
+  int32_t* X;            // [B, L] by slot
+  int32_t* age_w;        // [B, L] by slot
+  int32_t* verified;     // [B]
+  int32_t* accept_len;   // [B]
+  int32_t* out;          // [B, N]
+  int rows;              // select-only: rows; else B*L
+  int B, L, N, n, top_k, v_lo;
+  uint64_t seed;
+};
+size_t row_kernel_lds_bytes(int n);
+hipError_t launch_row(const RowArgs& a, hipStream_t s);
+
 // ---- first rejection, emit, slide -----------------------------------------
 struct CommitArgs {
   const uint8_t* k;     // [B, L]
@@ -80,7 +118,7 @@ hipError_t launch_commit(const CommitArgs& a, hipStream_t s);
 // ---- state initialisation / logits copy-in --------------------------------
 struct ResetArgs {
   int32_t* pos; int32_t* iter; int32_t* X; int32_t* age; int32_t* out; int32_t* accept_len;
-  int32_t* verified; int32_t* flags;
+  int32_t* verified; int32_t* flags; int32_t* ticket;
   int B, L, N, n;
   uint64_t seed;
 };

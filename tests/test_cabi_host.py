@@ -75,7 +75,7 @@ def test_create_rejects_bad_arguments_without_touching_the_device():
     total = B.state_bytes(cfg)
     base = 0x100000
     spans = []
-    for f in range(16):
+    for f in range(17):
         p, nb = ctypes.c_void_p(), ctypes.c_size_t()
         assert lib.scd_state_field(ctx, ctypes.c_void_p(base), f, ctypes.byref(p), ctypes.byref(nb)) == 0
         assert p.value % 256 == 0 and nb.value > 0
@@ -83,7 +83,7 @@ def test_create_rejects_bad_arguments_without_touching_the_device():
     spans.sort()
     assert spans[-1][1] <= total
     assert all(a[1] <= b[0] for a, b in zip(spans, spans[1:]))
-    assert lib.scd_state_field(ctx, ctypes.c_void_p(base), 16, ctypes.byref(p), ctypes.byref(nb)) == B.SCD_EINVAL
+    assert lib.scd_state_field(ctx, ctypes.c_void_p(base), 17, ctypes.byref(p), ctypes.byref(nb)) == B.SCD_EINVAL
     assert lib.scd_destroy(ctx) == B.SCD_OK
     assert lib.scd_destroy(None) == B.SCD_EINVAL
     assert B.strerror(B.SCD_EWORKSPACE).startswith("workspace")

@@ -196,6 +196,8 @@ def test_lockstep_C0_full_and_golden():
     dict(N=70, L=8, seed=15, B=3, V=1000),          # batch, ragged n
     dict(N=64, L=64, seed=16, top_k=10, V=300),
     dict(N=300, L=128, seed=17, V=512),             # window longer than a wavefront
+    dict(N=12, L=4, seed=18, V=70000, top_k=500, age_cap=4),   # rows too long for the LDS-resident kernel
+    dict(N=20, L=4, seed=19, V=65536, top_k=2000, age_cap=4),  # longest row of the LDS-resident kernel
 ])
 def test_lockstep_toy_variants(kw):
     _lockstep(wl.scaled(wl.WORKLOADS["C0"], name="toy", **kw))
