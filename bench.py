@@ -39,6 +39,9 @@ def parse():
                     help="C1 | C2 | C2-fullV | C3 | C4 (see paper_2510_24211_amd/workload.py)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=15.0)
+    ap.add_argument("--quick", action="store_true",
+                    help="profiling aid: skip the whole-decode warm-up, run --warmup then --steps "
+                         "iterations from a fresh state (both must be given and fit in one decode)")
     ap.add_argument("--no-events", action="store_true",
                     help="do not record the per-step LM-head events (roofline from a second pass)")
     return ap.parse_args()
@@ -161,20 +164,26 @@ def main():
             if flags[1]:
                 return flags[2]
 
-    nfe = decode_to_end()                         # also the warm-up when --warmup 0
-    verified_per_decode = int(s.state_field(st, B.F_VERIFIED).sum().item())
+    if a.quick:
+        assert a.steps > 0 and a.warmup > 0, "--quick needs --steps and --warmup"
+        nfe, verified_per_decode = 1 << 30, 0
+    else:
+        nfe = decode_to_end()                     # also the warm-up when --warmup 0
+        verified_per_decode = int(s.state_field(st, B.F_VERIFIED).sum().item())
     K = a.steps if a.steps > 0 else nfe
     Wm = a.warmup
     s.reset(st)
     if Wm > 0:
         run_steps(min(Wm, nfe))
-        s.reset(st)
+        if not a.quick:
+            s.reset(st)
 
     use_events = not a.no_events
     ev = HipEvents(K) if use_events else None
 
     def timed_pass(with_events):
-        s.reset(st)
+        if not a.quick:
+            s.reset(st)
         torch.cuda.synchronize()
         done_decodes, in_decode = 0, 0
         t0 = time.perf_counter()
@@ -234,7 +243,8 @@ def main():
         "config": {"workload": f"{w.name}: B={w.B} CFG={'on' if w.C == 2 else 'off'} L={w.L} "
                                f"N={w.N} V={w.V} allowed={n} d={w.d} top_k={w.top_k} "
                                f"lambda={w.cfg_lambda} seed={w.seed} (synthetic drift model)",
-                   "decode_iterations": int(nfe), "tokens_per_iteration": w.B * w.N / nfe,
+                   "decode_iterations": None if a.quick else int(nfe),
+                   "tokens_per_iteration": None if a.quick else w.B * w.N / nfe,
                    "step_bytes_algorithmic": alg_bytes + 2 * w.B * w.L * min(n, w.top_k or n) * 8,
                    "step_hbm_frac": (alg_bytes + 2 * w.B * w.L * min(n, w.top_k or n) * 8)
                    / (T / K) / 1e9 / HBM_PEAK_GBS,
