@@ -51,10 +51,11 @@ def load():
     global _lib
     if _lib is not None:
         return _lib
-    if not os.path.exists(LIB_PATH):
-        raise RuntimeError(f"{LIB_PATH} is missing: build it with "
+    path = os.environ.get("SCD_LIB", LIB_PATH)      # SCD_LIB: an alternative build of the library
+    if not os.path.exists(path):
+        raise RuntimeError(f"{path} is missing: build it with "
                            "`python -m paper_2510_24211_amd.build` (there is no CPU fallback)")
-    lib = ctypes.CDLL(LIB_PATH)
+    lib = ctypes.CDLL(path)
     vp, i32, sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_size_t
     cfgp = ctypes.POINTER(ScdConfig)
     lib.scd_workspace_bytes.restype = sz

@@ -1,6 +1,6 @@
-// Fused per-row kernel of the SCD step: top-k threshold, softmax normaliser,
-// Modified Rejection Sampling (accept test + residual resample) and -- through
-// a last-arriver ticket per sequence -- first rejection, emission and window
+// Per-row part of the SCD step: top-k threshold, softmax normaliser, Modified
+// Rejection Sampling (accept test + residual resample) and -- through a
+// last-arriver ticket per sequence -- first rejection, emission and window
 // slide.  (Alg. 1; Sec. 4.3 "vectorizing verification loop without break and
 // saving the index where the first rejection occurs"; appendix "Algorithms",
 // Alg. SCD(pi_MC); top-k / temperature from the appendix "Experimental
@@ -10,28 +10,52 @@
 //   lse  = m + log sum_kept exp(z_v - m),  p_v = [z_v >= thr] exp(z_v - lse)
 //   accept iff fl(u * q(x)) <= p(x);  else y = argmin_{r_v > 0} -ln(U_v) / r_v
 //
-// gfx950 mapping.  One workgroup (16 wavefronts) per window position.  The row
-// is read from memory ONCE, coalesced: the upper 16 bits of each logit's
-// order-preserving key are parked in LDS (2 bytes per id, 128 KB for 65536
-// ids).  Everything after that works on the LDS copy:
-//   * the K-th largest 16-bit prefix by counting in an LDS histogram whose bins
-//     are (prefix - min) >> s, i.e. spread over the row's actual range, so that
-//     lanes rarely collide on a bin;
-//   * the low 16 bits of the threshold, the sum of exponentials and the
-//     residual race touch memory only for ids whose prefix is >= the
-//     threshold's (about K of n ids).
-// All counting is integer, all floating-point sums use a fixed assignment of
-// ids to threads and a fixed reduction tree: results are run-to-run identical.
+// gfx950 mapping.  A row of up to 65536 logits is far more than one CU should
+// chew through alone (a CU retires 64 lane-operations per clock), and with few
+// sequences there are few rows, so the work is cut in two:
+//   slice_kernel  rows x P workgroups.  Each holds 1/P of a row in registers
+//                 (8 logits per thread), finds the slice's r-th largest key
+//                 exactly (r ~ 2K/P) and emits the (id, logit) pairs above it.
+//                 The union of the emitted sets contains the row's top K unless
+//                 one slice holds more than r of them.
+//   row_kernel    one workgroup per row.  Loads the <= 6144 candidates into
+//                 registers (6 per thread), selects the K-th largest key among
+//                 them, and accepts the answer only if it is >= every slice's
+//                 cut (then no unseen logit can be >= it): exact, verified.
+//                 Sum of exponentials, accept test, residual race and the
+//                 commit follow from the same registers.
+// Rows of <= 8192 logits skip the slice kernel (the whole row fits the row
+// kernel's registers).  If the verification fails (massive ties, adversarial
+// layouts) or top-k is off, the row kernel falls back to a complete in-place
+// path: one coalesced read of the row, 16-bit key prefixes parked in LDS,
+// histogram select, candidate list or in-place scans.
+// The K-th largest key is always found by integer counting (LDS histograms
+// whose bins adapt to the key range, so lanes rarely collide); all
+// floating-point sums use a fixed assignment of ids to threads and a fixed
+// reduction tree, so results are run-to-run identical.
 #include "scd_device.h"
 #include "scd_kernels.h"
 
 namespace scd {
 namespace {
 
-constexpr int THREADS = 1024;
+#ifndef SCD_ROW_THREADS
+#define SCD_ROW_THREADS 1024
+#endif
+// Few, fat threads: the per-wavefront bookkeeping (scans, reductions, the accept draw)
+// costs issue slots per wavefront, the per-logit work does not care how it is cut.
+constexpr int THREADS = SCD_ROW_THREADS;
 constexpr int NW = THREADS / kWave;
 constexpr int NBINS = 4096;
-constexpr int kListCap = 6144;     // candidate ids kept in LDS (uint16 each)
+constexpr int kListCap = 6144;               // candidate ids per row (LDS list / slice output)
+constexpr int PER_LIST = kListCap / THREADS; // candidates per thread
+constexpr int kDirectMaxN = 8192;            // whole row in registers up to this many ids
+constexpr int PER_DIRECT = kDirectMaxN / THREADS;
+constexpr int kSliceMax = 8192;              // logits per slice workgroup
+constexpr int PER_SLICE = kSliceMax / THREADS;
+static_assert(THREADS >= 256 && kListCap % THREADS == 0 && PER_DIRECT % 4 == 0 && PER_SLICE % 4 == 0,
+              "row kernels: unsupported workgroup size");
+constexpr int kKeptCap = 4096;               // kept ids compacted in LDS
 
 struct Small {
   float fred[NW];
@@ -101,81 +125,447 @@ __device__ __forceinline__ float prob(float z, float thr, float lse) {
   return z >= thr ? expf(z - lse) : 0.f;
 }
 
-__global__ __launch_bounds__(THREADS) void row_kernel(const RowArgs a) {
-  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+// Exclusive offset of this thread's `cnt` in a fixed thread order, and the total.
+__device__ __forceinline__ int block_offsets(int cnt, int& total, Small& sm) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  int incl = cnt;
+#pragma unroll
+  for (int o = 1; o < 64; o <<= 1) {
+    const int t = __shfl_up(incl, o, kWave);
+    if (lane >= o) incl += t;
+  }
+  if (lane == 63) sm.ired[wave] = incl;
+  __syncthreads();
+  int base = 0;
+  total = 0;
+#pragma unroll
+  for (int w = 0; w < NW; ++w) {
+    base += w < wave ? sm.ired[w] : 0;
+    total += sm.ired[w];
+  }
+  __syncthreads();
+  return base + incl - cnt;
+}
+
+// max / min of keys over the workgroup
+__device__ __forceinline__ void block_minmax(uint32_t& kmin, uint32_t& kmax, Small& sm) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  kmax = wave_max_u32(kmax);
+  kmin = ~wave_max_u32(~kmin);
+  if (lane == 0) {
+    sm.umax[wave] = kmax;
+    sm.umin[wave] = kmin;
+  }
+  __syncthreads();
+#pragma unroll
+  for (int w = 0; w < NW; ++w) {
+    kmax = sm.umax[w] > kmax ? sm.umax[w] : kmax;
+    kmin = sm.umin[w] < kmin ? sm.umin[w] : kmin;
+  }
+  __syncthreads();
+}
+
+// `need`-th largest key among the register-resident logits zv[e] (keys kv[e], valid
+// where ok[e]).  kmin_in is the smallest key among the valid logits above -1e30,
+// kmax the largest key (both from block_minmax).
+//   Level 1 bins the logits LINEARLY in value between those two (any monotone map
+//   of the value preserves the order statistic; a linear one spreads a bell-shaped
+//   row over all bins, where the float bit pattern would pile it into a few
+//   exponent bins and serialise the LDS atomics).
+//   Level 2 ranks the handful of members of the selected bin against each other.
+//   Should that bin hold more than NBINS members (massive ties), radix levels over
+//   the key bits finish the job.
+constexpr float kRangeFloor = -1.0e30f;
+template <int PER>
+__device__ __forceinline__ uint32_t select_regs(const float (&zv)[PER], const uint32_t (&kv)[PER],
+                                                const bool (&ok)[PER], uint32_t kmin_in,
+                                                uint32_t kmax, uint32_t need, uint32_t* hist,
+                                                Small& sm) {
+  const float zlo = key_to_float(kmin_in), zhi = key_to_float(kmax);
+  const float scale = (zhi > zlo) ? __fdiv_rn(static_cast<float>(NBINS - 1), zhi - zlo) : 0.f;
+  int bin[PER];
+#pragma unroll
+  for (int e = 0; e < PER; ++e) {
+    int bb = 0;
+    if (ok[e] && zv[e] > kRangeFloor) {
+      const float t = (zv[e] - zlo) * scale;
+      bb = t >= 0.f ? (t >= static_cast<float>(NBINS - 1) ? NBINS - 1 : static_cast<int>(t)) : 0;
+    }
+    bin[e] = bb;
+  }
+  zero_hist(hist);
+  __syncthreads();
+#pragma unroll
+  for (int e = 0; e < PER; ++e)
+    if (ok[e]) atomicAdd(&hist[bin[e]], 1u);
+  __syncthreads();
+  const int b1 = static_cast<int>(find_bin(hist, need, sm));
+  const uint32_t members = hist[b1];
+  if (threadIdx.x == 0) sm.sel_above = 0u;       // append cursor
+  __syncthreads();
+  if (members <= static_cast<uint32_t>(NBINS)) {
+    uint32_t* arr = hist;                        // the histogram is spent: reuse it for the keys
+#pragma unroll
+    for (int e = 0; e < PER; ++e)
+      if (ok[e] && bin[e] == b1) arr[atomicAdd(&sm.sel_above, 1u)] = kv[e];
+    __syncthreads();
+#pragma unroll
+    for (int e = 0; e < PER; ++e) {
+      if (ok[e] && bin[e] == b1) {
+        uint32_t gt = 0, ge = 0;
+        for (uint32_t i = 0; i < members; ++i) {
+          const uint32_t k = arr[i];
+          gt += k > kv[e] ? 1u : 0u;
+          ge += k >= kv[e] ? 1u : 0u;
+        }
+        if (gt < need && need <= ge) sm.sel_bin = kv[e];   // equal keys write the same value
+      }
+    }
+    __syncthreads();
+    const uint32_t res = sm.sel_bin;
+    __syncthreads();
+    return res;
+  }
+  // radix levels over the key bits of the members, range [lo, lo + width)
+  uint32_t lo = 0;
+  uint64_t width = 1ull << 32;
+  for (;;) {
+    int s2 = 0;
+    while (((width - 1) >> s2) >= static_cast<uint64_t>(NBINS)) ++s2;
+    zero_hist(hist);
+    __syncthreads();
+#pragma unroll
+    for (int e = 0; e < PER; ++e) {
+      if (ok[e] && bin[e] == b1 && kv[e] >= lo && static_cast<uint64_t>(kv[e] - lo) < width)
+        atomicAdd(&hist[(kv[e] - lo) >> s2], 1u);
+    }
+    __syncthreads();
+    const uint32_t dgt = find_bin(hist, need, sm);
+    lo += dgt << s2;
+    width = 1ull << s2;
+    if (s2 == 0) return lo;
+  }
+}
+
+// Where a kernel instance finds its row.
+struct RowRef {
+  const float* zc;
+  const float* zp;
+  float thr_p, lse_p;
+  bool fresh, active;
+  int x, b, s, p0, live, it;
+  size_t widx, oidx;
+};
+
+__device__ __forceinline__ RowRef locate_row(const RowArgs& a, int r) {
+  RowRef R{};
+  R.widx = r;
+  R.oidx = r;
+  R.it = a.iter_scalar;
+  R.x = -1;
+  R.active = true;
+  const int n = a.n;
+  if (a.mode == kRowSelectOnly) {
+    R.zc = a.z_cur + static_cast<size_t>(r) * n;
+    return R;
+  }
+  R.b = r / a.L;
+  R.s = r % a.L;
+  R.p0 = a.pos[R.b];
+  R.live = max(0, min(a.L, a.N - R.p0));
+  R.widx = static_cast<size_t>(R.b) * a.L + R.s;
+  if (R.s >= R.live) {
+    R.active = false;
+    return R;
+  }
+  if (a.mode == kRowRing) {
+    R.it = a.iter[R.b];
+    const int par = R.it & 1;
+    const size_t sidx = static_cast<size_t>(R.b) * a.L + (R.p0 + R.s) % a.L;
+    const size_t half = static_cast<size_t>(a.B) * a.L;
+    R.oidx = par * half + sidx;
+    R.x = a.x[sidx];
+    R.fresh = a.age[sidx] == 0;
+    R.zc = a.z_cur + static_cast<size_t>(par) * a.parity_stride + sidx * n;
+    R.zp = a.z_cur + static_cast<size_t>(par ^ 1) * a.parity_stride + sidx * n;
+    if (!R.fresh) {
+      R.thr_p = a.thr[(par ^ 1) * half + sidx];
+      R.lse_p = a.lse[(par ^ 1) * half + sidx];
+    }
+  } else {
+    R.oidx = R.widx;
+    R.x = a.x[R.widx];
+    R.fresh = a.fresh ? a.fresh[R.widx] != 0 : false;
+    R.zc = a.z_cur + R.widx * n;
+    R.zp = a.z_prev + R.widx * n;
+    if (!R.fresh) {
+      R.thr_p = a.thr_prev[R.widx];
+      R.lse_p = a.lse_prev[R.widx];
+    }
+  }
+  return R;
+}
+
+// ---------------------------------------------------------------------------------
+// slice kernel
+// ---------------------------------------------------------------------------------
+__global__ __launch_bounds__(THREADS) void slice_kernel(const RowArgs a, const int P, const int capE,
+                                                        const int rank) {
+  __shared__ uint32_t hist[NBINS];
   __shared__ Small sm;
+  const int tid = threadIdx.x;
+  const int r = blockIdx.x / P, p = blockIdx.x % P;
+  const RowRef R = locate_row(a, r);
+  if (!R.active) return;
+  const int n = a.n;
+  const int slice_len = (((n + P - 1) / P) + 3) & ~3;
+  const int lo_id = p * slice_len;
+  const int hi_id = min(n, lo_id + slice_len);
+  uint32_t* const cnt_out = a.cand_cnt + static_cast<size_t>(r) * 8;
+  uint32_t* const cut_out = a.cand_cut + static_cast<size_t>(r) * 8;
+  if (lo_id >= hi_id) {
+    if (tid == 0) {
+      cnt_out[p] = 0;
+      cut_out[p] = 0;
+    }
+    return;
+  }
+  const bool vec_ok = (n & 3) == 0;
+  float zv[PER_SLICE];
+  int vid[PER_SLICE];
+  bool ok[PER_SLICE];
+#pragma unroll
+  for (int u = 0; u < PER_SLICE / 4; ++u) {
+    const int v0 = lo_id + ((tid + u * THREADS) << 2);
+    if (vec_ok && v0 + 3 < hi_id) {
+      const float4 t = *reinterpret_cast<const float4*>(R.zc + v0);
+      zv[u * 4 + 0] = t.x; zv[u * 4 + 1] = t.y; zv[u * 4 + 2] = t.z; zv[u * 4 + 3] = t.w;
+    } else {
+#pragma unroll
+      for (int e = 0; e < 4; ++e) zv[u * 4 + e] = (v0 + e < hi_id) ? R.zc[v0 + e] : 0.f;
+    }
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      vid[u * 4 + e] = v0 + e;
+      ok[u * 4 + e] = v0 + e < hi_id;
+    }
+  }
+  uint32_t kv[PER_SLICE], kmax = 0, kmin = 0xFFFFFFFFu;
+#pragma unroll
+  for (int e = 0; e < PER_SLICE; ++e) {
+    kv[e] = zkey(zv[e]);
+    if (ok[e]) {
+      kmax = kv[e] > kmax ? kv[e] : kmax;
+      if (zv[e] > kRangeFloor) kmin = kv[e] < kmin ? kv[e] : kmin;
+      if (zv[e] != zv[e] && a.flags) atomicOr(a.flags, 1);     // NaN of either sign
+    }
+  }
+  block_minmax(kmin, kmax, sm);
+  const int nvalid = hi_id - lo_id;
+  uint32_t cut = 0;                       // 0: the whole slice is emitted
+  if (nvalid > rank) cut = select_regs<PER_SLICE>(zv, kv, ok, kmin, kmax, static_cast<uint32_t>(rank), hist, sm);
+  int mine = 0;
+#pragma unroll
+  for (int e = 0; e < PER_SLICE; ++e) mine += (ok[e] && kv[e] >= cut) ? 1 : 0;
+  int total;
+  int off = block_offsets(mine, total, sm);
+  uint2* const dst = a.cand + (static_cast<size_t>(r) * kListCap + static_cast<size_t>(p) * capE);
+#pragma unroll
+  for (int e = 0; e < PER_SLICE; ++e) {
+    if (ok[e] && kv[e] >= cut) {
+      if (off < capE) dst[off] = make_uint2(static_cast<uint32_t>(vid[e]), __float_as_uint(zv[e]));
+      ++off;
+    }
+  }
+  if (tid == 0) {
+    cnt_out[p] = static_cast<uint32_t>(total);   // > capE signals overflow
+    cut_out[p] = cut;
+  }
+}
+
+// ---------------------------------------------------------------------------------
+// row kernel
+// ---------------------------------------------------------------------------------
+struct RowOut {      // what a path hands to the common tail
+  bool accept;
+  float px, qx;
+  float best;
+  int best_id;
+};
+
+// Everything after the candidates sit in registers: threshold (if top-k filters),
+// normaliser, accept test, residual race.  Returns false if the threshold could not
+// be certified against `cut_max` (the caller then takes the complete path).
+template <int PER>
+__device__ __forceinline__ bool finish_regs(const RowArgs& a, const RowRef& R, const int (&vid)[PER],
+                                            const float (&zv)[PER], const bool (&ok)[PER],
+                                            bool filter, uint32_t cut_max, float zcx, float zpx,
+                                            uint32_t* hist, uint32_t* cid, float* cz, int ccap,
+                                            Small& sm, RowOut& out) {
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int n = a.n;
-  const int n8 = (n + 7) & ~7;                       // prefix array padded to 8 entries
-  uint16_t* k16 = reinterpret_cast<uint16_t*>(smem);
-  uint32_t* hist = reinterpret_cast<uint32_t*>(smem + static_cast<size_t>(n8) * 2);
-  uint16_t* list = reinterpret_cast<uint16_t*>(smem + static_cast<size_t>(n8) * 2 + NBINS * 4);
-
-  // ---- which row ---------------------------------------------------------
-  const int r = blockIdx.x;
-  int b = 0, s = 0, p0 = 0, live = 0, it = a.iter_scalar;
-  size_t widx = r, oidx = r;
-  const float* zc;
-  const float* zp = nullptr;
-  float thr_p = 0.f, lse_p = 0.f;
-  bool fresh = false;
-  int x = -1;
-  if (a.mode == kRowSelectOnly) {
-    zc = a.z_cur + static_cast<size_t>(r) * n;
-  } else {
-    b = r / a.L;
-    s = r % a.L;
-    p0 = a.pos[b];
-    live = max(0, min(a.L, a.N - p0));
-    widx = static_cast<size_t>(b) * a.L + s;
-    if (s >= live) {
-      if (tid == 0) {
-        a.y[widx] = -1;
-        a.k[widx] = 1;
-        if (a.px) a.px[widx] = 0.f;
-        if (a.qx) a.qx[widx] = 0.f;
-        if (a.mode == kRowRing && s == 0) a.accept_len[b] = 0;   // finished sequence
-      }
-      return;
+  uint32_t kv[PER], kmax = 0, kmin = 0xFFFFFFFFu;
+#pragma unroll
+  for (int e = 0; e < PER; ++e) {
+    kv[e] = zkey(zv[e]);
+    if (ok[e]) {
+      kmax = kv[e] > kmax ? kv[e] : kmax;
+      if (zv[e] > kRangeFloor) kmin = kv[e] < kmin ? kv[e] : kmin;
+      if (zv[e] != zv[e] && a.flags) atomicOr(a.flags, 1);     // NaN of either sign
     }
-    if (a.mode == kRowRing) {
-      it = a.iter[b];
-      const int par = it & 1;
-      const size_t sidx = static_cast<size_t>(b) * a.L + (p0 + s) % a.L;
-      const size_t half = static_cast<size_t>(a.B) * a.L;
-      oidx = par * half + sidx;
-      x = a.x[sidx];
-      fresh = a.age[sidx] == 0;
-      zc = a.z_cur + static_cast<size_t>(par) * a.parity_stride + sidx * n;
-      zp = a.z_cur + static_cast<size_t>(par ^ 1) * a.parity_stride + sidx * n;
-      if (!fresh) {
-        thr_p = a.thr[(par ^ 1) * half + sidx];
-        lse_p = a.lse[(par ^ 1) * half + sidx];
+  }
+  block_minmax(kmin, kmax, sm);
+  const float m = key_to_float(kmax);
+  float thr = -INFINITY;
+  if (filter) {
+    const uint32_t tkey = select_regs<PER>(zv, kv, ok, kmin, kmax, static_cast<uint32_t>(a.top_k), hist, sm);
+    if (tkey < cut_max) return false;     // an unseen logit could be >= the K-th candidate
+    thr = key_to_float(tkey);
+  }
+  // Kept ids are a random ~K/n of each thread's logits; compacting them into LDS (count /
+  // scan / write: a fixed order) lets the expensive per-id work that follows be dealt out
+  // evenly, kKeptPer per thread, instead of at the pace of the unluckiest lane.
+  bool kept[PER];
+  int mine = 0;
+#pragma unroll
+  for (int e = 0; e < PER; ++e) {
+    kept[e] = ok[e] && zv[e] >= thr;
+    mine += kept[e] ? 1 : 0;
+  }
+  int Cn;
+  int off = block_offsets(mine, Cn, sm);
+  const bool compact = Cn <= ccap;
+  if (compact) {
+#pragma unroll
+    for (int e = 0; e < PER; ++e) {
+      if (kept[e]) {
+        cid[off] = static_cast<uint32_t>(vid[e]);
+        cz[off] = zv[e];
+        ++off;
       }
-    } else {
-      oidx = widx;
-      x = a.x[widx];
-      fresh = a.fresh ? a.fresh[widx] != 0 : false;
-      zc = a.z_cur + widx * n;
-      zp = a.z_prev + widx * n;
-      if (!fresh) {
-        thr_p = a.thr_prev[widx];
-        lse_p = a.lse_prev[widx];
+    }
+    __syncthreads();
+  }
+  float sum = 0.f;
+  if (compact) {
+    for (int i = tid; i < Cn; i += THREADS) sum += expf(cz[i] - m);
+  } else {
+#pragma unroll
+    for (int e = 0; e < PER; ++e)
+      if (kept[e]) sum += expf(zv[e] - m);
+  }
+  sum = wave_sum(sum);
+  if (lane == 0) sm.fred[wave] = sum;
+  __syncthreads();
+  float S = 0.f;
+#pragma unroll
+  for (int w = 0; w < NW; ++w) S += sm.fred[w];
+  const float lse_c = m + logf(S);
+  if (tid == 0) {
+    a.thr[R.oidx] = thr;
+    a.lse[R.oidx] = lse_c;
+    a.nkept[R.oidx] = Cn;
+    if (a.flags && !(lse_c == lse_c && fabsf(lse_c) < INFINITY)) atomicOr(a.flags, 1);
+  }
+  if (a.mode == kRowSelectOnly) return true;
+
+  // Modified Rejection Sampling
+  const int j = R.p0 + R.s;
+  const float q_uniform = __fdiv_rn(1.0f, static_cast<float>(n));
+  const uint2 key = seed_key(a.seed);
+  const uint32_t w3 = static_cast<uint32_t>(R.b) << 8;
+  const bool x_ok = R.x >= 0 && R.x < n;
+  out.px = x_ok ? prob(zcx, thr, lse_c) : 0.f;
+  out.qx = R.fresh ? q_uniform : (x_ok ? prob(zpx, R.thr_p, R.lse_p) : 0.f);
+  const uint4 ra = philox4x32_10(make_uint4(0u, static_cast<uint32_t>(j), static_cast<uint32_t>(R.it),
+                                            w3 | kStreamAccept), key);
+  out.accept = __fmul_rn(u01(ra.x), out.qx) <= out.px;
+  out.best = INFINITY;
+  out.best_id = 0x7FFFFFFF;
+  if (out.accept) return true;     // uniform over the workgroup
+
+  auto race_one = [&](int v, float rv) {   // exponential-race entry of id v, residual rv > 0
+    const uint4 rr = philox4x32_10(make_uint4(static_cast<uint32_t>(v >> 2), static_cast<uint32_t>(j),
+                                              static_cast<uint32_t>(R.it), w3 | kStreamResid), key);
+    const uint32_t lanes[4] = {rr.x, rr.y, rr.z, rr.w};
+    const float sc = __fdiv_rn(-logf(u01(lanes[v & 3])), rv);
+    if (sc < out.best || (sc == out.best && v < out.best_id)) {
+      out.best = sc;
+      out.best_id = v;
+    }
+  };
+  if (compact) {
+    // residuals r = p - q of the kept ids, then a second compaction of the positive ones
+    constexpr int KPT = kKeptCap / THREADS;   // ccap <= KPT * THREADS
+    int rid[KPT];
+    float rz[KPT], rq[KPT];
+#pragma unroll
+    for (int q = 0; q < KPT; ++q) {
+      const int i = tid + q * THREADS;
+      rid[q] = i < Cn ? static_cast<int>(cid[i]) : -1;
+      rz[q] = i < Cn ? cz[i] : 0.f;
+    }
+#pragma unroll
+    for (int q = 0; q < KPT; ++q) rq[q] = (!R.fresh && rid[q] >= 0) ? R.zp[rid[q]] : 0.f;
+    int npos = 0;
+#pragma unroll
+    for (int q = 0; q < KPT; ++q) {
+      float rv = 0.f;
+      if (rid[q] >= 0) {
+        const float pv = expf(rz[q] - lse_c);
+        const float qv = R.fresh ? q_uniform : prob(rq[q], R.thr_p, R.lse_p);
+        rv = __fsub_rn(pv, qv);
+      }
+      rz[q] = rv;
+      npos += rv > 0.f ? 1 : 0;
+    }
+    int ntot;
+    int o2 = block_offsets(npos, ntot, sm);        // its barriers also end every read of cid / cz
+#pragma unroll
+    for (int q = 0; q < KPT; ++q) {
+      if (rz[q] > 0.f) {
+        cid[o2] = static_cast<uint32_t>(rid[q]);
+        cz[o2] = rz[q];
+        ++o2;
+      }
+    }
+    __syncthreads();
+    for (int i = tid; i < ntot; i += THREADS) race_one(static_cast<int>(cid[i]), cz[i]);
+  } else {
+    float zq[PER];
+#pragma unroll
+    for (int e = 0; e < PER; ++e) zq[e] = (!R.fresh && kept[e]) ? R.zp[vid[e]] : 0.f;
+#pragma unroll
+    for (int e = 0; e < PER; ++e) {
+      if (kept[e]) {
+        const float pv = expf(zv[e] - lse_c);
+        const float qv = R.fresh ? q_uniform : prob(zq[e], R.thr_p, R.lse_p);
+        const float rv = __fsub_rn(pv, qv);
+        if (rv > 0.f) race_one(vid[e], rv);
       }
     }
   }
+  return true;
+}
 
-  // Prefetch the two logits of the draft token so that their latency hides
-  // behind the row pass.
-  const bool x_ok = a.mode != kRowSelectOnly && x >= 0 && x < n;
-  const float zcx = x_ok ? zc[x] : 0.f;
-  const float zpx = (x_ok && !fresh) ? zp[x] : 0.f;
+// The complete in-place path: one coalesced read of the row, 16-bit key prefixes in
+// LDS, histogram select; then a candidate list in registers, or in-place scans when
+// top-k is off or the candidates do not fit.
+__device__ __forceinline__ void full_path(const RowArgs& a, const RowRef& R, unsigned char* smem,
+                                          float zcx, float zpx, Small& sm, RowOut& out) {
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int n = a.n;
+  const int n8 = (n + 7) & ~7;
+  uint16_t* k16 = reinterpret_cast<uint16_t*>(smem);
+  uint32_t* hist = reinterpret_cast<uint32_t*>(smem + static_cast<size_t>(n8) * 2);
+  uint16_t* list = reinterpret_cast<uint16_t*>(smem + static_cast<size_t>(n8) * 2 + NBINS * 4);
+  const float* zc = R.zc;
+  const float* zp = R.zp;
 
-  // ---- pass 1: the only full read of the row ------------------------------
-  // Batches of 8 independent 16-byte loads per thread keep 128 KB in flight.
+  // pass 1: batches of 8 independent 16-byte loads per thread
   const bool vec_ok = (n & 3) == 0;
-  const int ngroups = (n + 3) >> 2;          // groups of 4 ids holding at least one id
-  const int ngroups8 = n8 >> 2;              // groups covering the padded LDS array
+  const int ngroups = (n + 3) >> 2;
+  const int ngroups8 = n8 >> 2;
   uint32_t kmax = 0, p16min = 0xFFFFu, p16max = 0u;
   constexpr int UNR = 8;
   for (int g0 = tid; g0 < ngroups8; g0 += THREADS * UNR) {
@@ -203,6 +593,7 @@ __global__ __launch_bounds__(THREADS) void row_kernel(const RowArgs a) {
           const uint32_t key = zkey(f[u][e]);
           h[e] = key >> 16;
           if (v0 + e < n) {
+            if (f[u][e] != f[u][e] && a.flags) atomicOr(a.flags, 1);   // NaN of either sign
             kmax = key > kmax ? key : kmax;
             p16min = h[e] < p16min ? h[e] : p16min;
             p16max = h[e] > p16max ? h[e] : p16max;
@@ -213,37 +604,23 @@ __global__ __launch_bounds__(THREADS) void row_kernel(const RowArgs a) {
     }
   }
   kmax = wave_max_u32(kmax);
-  p16max = wave_max_u32(p16max);
-  p16min = ~wave_max_u32(~p16min);
-  if (lane == 0) {
-    sm.ured[wave] = kmax;
-    sm.umax[wave] = p16max;
-    sm.umin[wave] = p16min;
-  }
-  __syncthreads();
+  if (lane == 0) sm.ured[wave] = kmax;
+  block_minmax(p16min, p16max, sm);      // its barriers also publish ured and the LDS prefixes
 #pragma unroll
-  for (int w = 0; w < NW; ++w) {
-    kmax = sm.ured[w] > kmax ? sm.ured[w] : kmax;
-    p16max = sm.umax[w] > p16max ? sm.umax[w] : p16max;
-    p16min = sm.umin[w] < p16min ? sm.umin[w] : p16min;
-  }
+  for (int w = 0; w < NW; ++w) kmax = sm.ured[w] > kmax ? sm.ured[w] : kmax;
   const float m = key_to_float(kmax);
 
-  // Each thread owns the 8-id chunks c = tid, tid + THREADS, ... of the LDS copy.
-  const int nchunks = n8 >> 3;
+  const int nchunks = n8 >> 3;           // thread owns the 8-id chunks tid, tid + THREADS, ...
   const bool filter = a.top_k > 0 && a.top_k < n;
   const uint32_t K = static_cast<uint32_t>(a.top_k);
-
-  // prefix histogram over chunks [0, upto): bins = (prefix - min) >> sh, optionally
-  // only the prefixes that fall into bin `only` (then the bins are the sh low bits)
   const uint32_t range = p16max - p16min;
   int sh = 0;
   while ((range >> sh) >= static_cast<uint32_t>(NBINS)) ++sh;
-  auto prefix_hist = [&](int upto, bool low_bits, uint32_t only) {
+  auto prefix_hist = [&](bool low_bits, uint32_t only) {
     zero_hist(hist);
     __syncthreads();
     const uint32_t mask = (1u << sh) - 1u;
-    for (int c = tid; c < upto; c += THREADS) {
+    for (int c = tid; c < nchunks; c += THREADS) {
       const uint4 raw = *reinterpret_cast<const uint4*>(&k16[c << 3]);
       const uint32_t w4[4] = {raw.x, raw.y, raw.z, raw.w};
 #pragma unroll
@@ -257,287 +634,254 @@ __global__ __launch_bounds__(THREADS) void row_kernel(const RowArgs a) {
     }
     __syncthreads();
   };
-  // number of ids whose prefix is >= lowp: this thread's share, its exclusive
-  // offset in a fixed order, and the total
-  int my_cnt = 0, my_off = 0, ncand = 0;
-  auto count_ge = [&](uint32_t lowp) {
-    my_cnt = 0;
+  uint32_t t16 = 0, need_ab = K;
+  int ncand = 0, my_off = 0;
+  bool use_list = false;
+  if (filter) {
+    prefix_hist(false, 0u);
+    const uint32_t binA = find_bin(hist, need_ab, sm);
+    uint32_t low = 0;
+    if (sh > 0) {
+      prefix_hist(true, binA);
+      low = find_bin(hist, need_ab, sm);
+    }
+    t16 = p16min + (binA << sh) + low;
+    int my_cnt = 0;
     for (int c = tid; c < nchunks; c += THREADS) {
       const uint4 raw = *reinterpret_cast<const uint4*>(&k16[c << 3]);
       const uint32_t w4[4] = {raw.x, raw.y, raw.z, raw.w};
 #pragma unroll
       for (int e = 0; e < 8; ++e) {
         const uint32_t p = (w4[e >> 1] >> ((e & 1) * 16)) & 0xFFFFu;
-        my_cnt += ((c << 3) + e < n && p >= lowp) ? 1 : 0;
+        my_cnt += ((c << 3) + e < n && p >= t16) ? 1 : 0;
       }
     }
-    int incl = my_cnt;
-#pragma unroll
-    for (int o = 1; o < 64; o <<= 1) {
-      const int t = __shfl_up(incl, o, kWave);
-      if (lane >= o) incl += t;
-    }
-    if (lane == 63) sm.ired[wave] = incl;
-    __syncthreads();
-    int base = 0;
-    ncand = 0;
-#pragma unroll
-    for (int w = 0; w < NW; ++w) {
-      base += w < wave ? sm.ired[w] : 0;
-      ncand += sm.ired[w];
-    }
-    my_off = base + incl - my_cnt;
-    __syncthreads();
-  };
-
-  // ---- a prefix bound `lowp` with K <= #{prefix >= lowp} -----------------------
-  uint32_t t16 = 0;         // exact 16-bit prefix of the threshold key (when computed)
-  uint32_t need_ab = K;     // rank still to resolve below t16's bin (in-place path)
-  bool exact16 = false;
-  uint32_t lowp = 0;
-  auto exact_prefix = [&]() {   // full histogram: exact 16-bit prefix of the K-th largest
-    need_ab = K;
-    prefix_hist(nchunks, false, 0u);
-    const uint32_t binA = find_bin(hist, need_ab, sm);
-    uint32_t low = 0;
-    if (sh > 0) {
-      prefix_hist(nchunks, true, binA);
-      low = find_bin(hist, need_ab, sm);
-    }
-    t16 = p16min + (binA << sh) + low;
-    exact16 = true;
-  };
-  bool use_list = false;
-  if (filter) {
-    if (nchunks <= THREADS) {
-      exact_prefix();
-      lowp = t16;
-      count_ge(lowp);
-    } else {
-      // The first THREADS chunks (8192 ids) act as a sample: the prefix bin of the
-      // sample's element of rank ~2K * 8192 / n is, almost always, a lower bound of
-      // the K-th largest of the row with about 2K ids above it.  The bound is
-      // verified by counting; if it fails the full histogram decides.
-      prefix_hist(THREADS, false, 0u);
-      const uint64_t target = min(static_cast<uint64_t>(2) * K, (static_cast<uint64_t>(K) + kListCap) / 2);
-      uint32_t ks = static_cast<uint32_t>(target * (THREADS * 8) / n);
-      ks = ks < 1 ? 1 : ks;
-      const uint32_t bs = find_bin(hist, ks, sm);
-      lowp = p16min + (bs << sh);
-      count_ge(lowp);
-      if (ncand < static_cast<int>(K) || ncand > kListCap) {
-        exact_prefix();
-        lowp = t16;
-        count_ge(lowp);
-      }
-    }
+    my_off = block_offsets(my_cnt, ncand, sm);
     use_list = ncand <= kListCap;
   }
 
-  float thr = -INFINITY;
-  float sum = 0.f;
-  int cnt = 0;
-  float best = INFINITY;        // residual race
-  int best_id = 0x7FFFFFFF;
-  const int j = p0 + s;
-  const float q_uniform = __fdiv_rn(1.0f, static_cast<float>(n));
-  const uint2 key = seed_key(a.seed);
-  const uint32_t w3 = static_cast<uint32_t>(b) << 8;
-  bool accept = true;
-  float px = 0.f, qx = 0.f;
-  auto race_one = [&](int v, float rv) {   // exponential race entry of id v with residual rv > 0
-    const uint4 rr = philox4x32_10(make_uint4(static_cast<uint32_t>(v >> 2), static_cast<uint32_t>(j),
-                                              static_cast<uint32_t>(it), w3 | kStreamResid), key);
-    const uint32_t lanes[4] = {rr.x, rr.y, rr.z, rr.w};
-    const float sc = __fdiv_rn(-logf(u01(lanes[v & 3])), rv);
-    if (sc < best || (sc == best && v < best_id)) {
-      best = sc;
-      best_id = v;
-    }
-  };
-  auto accept_test = [&](float thr_c, float lse_c) {
-    px = x_ok ? prob(zcx, thr_c, lse_c) : 0.f;
-    qx = fresh ? q_uniform : (x_ok ? prob(zpx, thr_p, lse_p) : 0.f);
-    const uint4 ra = philox4x32_10(make_uint4(0u, static_cast<uint32_t>(j), static_cast<uint32_t>(it),
-                                              w3 | kStreamAccept), key);
-    accept = __fmul_rn(u01(ra.x), qx) <= px;
-  };
-  float lse_c;
-
   if (use_list) {
-    // ======== candidates in registers: at most kListCap / THREADS = 6 per thread ====
-    constexpr int PER = kListCap / THREADS;
-    {
-      int o = my_off;
-      for (int c = tid; c < nchunks; c += THREADS) {
-        const uint4 raw = *reinterpret_cast<const uint4*>(&k16[c << 3]);
-        const uint32_t w4[4] = {raw.x, raw.y, raw.z, raw.w};
+    int o = my_off;
+    for (int c = tid; c < nchunks; c += THREADS) {
+      const uint4 raw = *reinterpret_cast<const uint4*>(&k16[c << 3]);
+      const uint32_t w4[4] = {raw.x, raw.y, raw.z, raw.w};
 #pragma unroll
-        for (int e = 0; e < 8; ++e) {
-          const uint32_t p = (w4[e >> 1] >> ((e & 1) * 16)) & 0xFFFFu;
-          if ((c << 3) + e < n && p >= lowp) list[o++] = static_cast<uint16_t>((c << 3) + e);
-        }
+      for (int e = 0; e < 8; ++e) {
+        const uint32_t p = (w4[e >> 1] >> ((e & 1) * 16)) & 0xFFFFu;
+        if ((c << 3) + e < n && p >= t16) list[o++] = static_cast<uint16_t>((c << 3) + e);
       }
     }
     __syncthreads();
-    int vid[PER];
-    float zv[PER];
-    uint32_t kv[PER];
+    int vid[PER_LIST];
+    float zv[PER_LIST];
+    bool ok[PER_LIST];
 #pragma unroll
-    for (int e = 0; e < PER; ++e) {
+    for (int e = 0; e < PER_LIST; ++e) {
       const int i = tid + e * THREADS;
-      vid[e] = i < ncand ? static_cast<int>(list[i]) : -1;
+      ok[e] = i < ncand;
+      vid[e] = ok[e] ? static_cast<int>(list[i]) : 0;
     }
 #pragma unroll
-    for (int e = 0; e < PER; ++e) zv[e] = vid[e] >= 0 ? zc[vid[e]] : 0.f;
-#pragma unroll
-    for (int e = 0; e < PER; ++e) kv[e] = zkey(zv[e]);
-    // K-th largest key among the candidates: range-adaptive radix levels
-    uint32_t lo = lowp << 16;
-    uint64_t width = static_cast<uint64_t>(kmax) - lo + 1;
-    uint32_t need = K;
-    for (;;) {
-      int s2 = 0;
-      while (((width - 1) >> s2) >= static_cast<uint64_t>(NBINS)) ++s2;
-      zero_hist(hist);
-      __syncthreads();
-#pragma unroll
-      for (int e = 0; e < PER; ++e) {
-        if (vid[e] >= 0 && kv[e] >= lo && static_cast<uint64_t>(kv[e] - lo) < width)
-          atomicAdd(&hist[(kv[e] - lo) >> s2], 1u);
-      }
-      __syncthreads();
-      const uint32_t dgt = find_bin(hist, need, sm);
-      lo += dgt << s2;
-      width = 1ull << s2;
-      if (s2 == 0) break;
-    }
-    thr = key_to_float(lo);
-#pragma unroll
-    for (int e = 0; e < PER; ++e) {
-      if (vid[e] >= 0 && zv[e] >= thr) {
-        sum += expf(zv[e] - m);
-        ++cnt;
-      }
-    }
-    sum = wave_sum(sum);
-    cnt = wave_sum_i32(cnt);
-    if (lane == 0) {
-      sm.fred[wave] = sum;
-      sm.ired[wave] = cnt;
-    }
-    __syncthreads();
-    float S = 0.f;
-    int Cn = 0;
-#pragma unroll
-    for (int w = 0; w < NW; ++w) {
-      S += sm.fred[w];
-      Cn += sm.ired[w];
-    }
-    lse_c = m + logf(S);
-    if (tid == 0) {
-      a.thr[oidx] = thr;
-      a.lse[oidx] = lse_c;
-      a.nkept[oidx] = Cn;
-      if (a.flags && !(lse_c == lse_c && fabsf(lse_c) < INFINITY)) atomicOr(a.flags, 1);
-    }
-    if (a.mode == kRowSelectOnly) return;
-    accept_test(thr, lse_c);
-    if (!accept) {     // uniform over the workgroup
-      float zq[PER];
-#pragma unroll
-      for (int e = 0; e < PER; ++e)
-        zq[e] = (!fresh && vid[e] >= 0 && zv[e] >= thr) ? zp[vid[e]] : 0.f;
-#pragma unroll
-      for (int e = 0; e < PER; ++e) {
-        if (vid[e] >= 0 && zv[e] >= thr) {
-          const float pv = expf(zv[e] - lse_c);
-          const float qv = fresh ? q_uniform : prob(zq[e], thr_p, lse_p);
-          const float rv = __fsub_rn(pv, qv);
-          if (rv > 0.f) race_one(vid[e], rv);
-        }
-      }
-    }
-  } else {
-    // ======== in place: no filter, or the candidates do not fit (massive ties) ======
-    if (filter && !exact16) exact_prefix();
-    auto for_each_candidate = [&](auto&& f) {
-      for (int c = tid; c < nchunks; c += THREADS) {
-        const uint4 raw = *reinterpret_cast<const uint4*>(&k16[c << 3]);
-        const uint32_t w4[4] = {raw.x, raw.y, raw.z, raw.w};
-#pragma unroll
-        for (int e = 0; e < 8; ++e) {
-          const int v = (c << 3) + e;
-          const uint32_t p = (w4[e >> 1] >> ((e & 1) * 16)) & 0xFFFFu;
-          if (v < n && (!filter || p >= t16)) f(v, p);
-        }
-      }
-    };
-    if (filter) {
-      // low 16 bits of the threshold key: two 8-bit digits over the ids whose prefix is t16
-      uint32_t lowkey = 0;
-#pragma unroll
-      for (int pass = 0; pass < 2; ++pass) {
-        zero_hist(hist);
-        __syncthreads();
-        const int shift = pass == 0 ? 8 : 0;
-        for_each_candidate([&](int v, uint32_t p) {
-          if (p == t16) {
-            const uint32_t kk = zkey(zc[v]) & 0xFFFFu;
-            if (pass == 0 || (kk >> 8) == (lowkey >> 8)) atomicAdd(&hist[(kk >> shift) & 0xFFu], 1u);
-          }
-        });
-        __syncthreads();
-        lowkey |= find_bin(hist, need_ab, sm) << shift;
-      }
-      thr = key_to_float((t16 << 16) | lowkey);
-    }
-    for_each_candidate([&](int v, uint32_t) {
-      const float z = zc[v];
-      if (z >= thr) {
-        sum += expf(z - m);
-        ++cnt;
-      }
-    });
-    sum = wave_sum(sum);
-    cnt = wave_sum_i32(cnt);
-    if (lane == 0) {
-      sm.fred[wave] = sum;
-      sm.ired[wave] = cnt;
-    }
-    __syncthreads();
-    float S = 0.f;
-    int Cn = 0;
-#pragma unroll
-    for (int w = 0; w < NW; ++w) {
-      S += sm.fred[w];
-      Cn += sm.ired[w];
-    }
-    lse_c = m + logf(S);
-    if (tid == 0) {
-      a.thr[oidx] = thr;
-      a.lse[oidx] = lse_c;
-      a.nkept[oidx] = Cn;
-      if (a.flags && !(lse_c == lse_c && fabsf(lse_c) < INFINITY)) atomicOr(a.flags, 1);
-    }
-    if (a.mode == kRowSelectOnly) return;
-    accept_test(thr, lse_c);
-    if (!accept) {
-      for_each_candidate([&](int v, uint32_t) {
-        const float pv = prob(zc[v], thr, lse_c);
-        if (pv > 0.f) {
-          const float qv = fresh ? q_uniform : prob(zp[v], thr_p, lse_p);
-          const float rv = __fsub_rn(pv, qv);
-          if (rv > 0.f) race_one(v, rv);
-        }
-      });
-    }
+    for (int e = 0; e < PER_LIST; ++e) zv[e] = ok[e] ? zc[vid[e]] : 0.f;
+    // the prefixes in LDS are spent: their space takes the compaction arrays
+    const int ccap = min(kKeptCap, static_cast<int>(static_cast<size_t>(n8) * 2 / 8));
+    finish_regs<PER_LIST>(a, R, vid, zv, ok, true, 0u, zcx, zpx, hist,
+                          reinterpret_cast<uint32_t*>(smem), reinterpret_cast<float*>(smem) + ccap, ccap, sm,
+                          out);
+    return;
   }
 
+  // in place: no filter, or the candidates do not fit (massive ties)
+  auto for_each_candidate = [&](auto&& f) {
+    for (int c = tid; c < nchunks; c += THREADS) {
+      const uint4 raw = *reinterpret_cast<const uint4*>(&k16[c << 3]);
+      const uint32_t w4[4] = {raw.x, raw.y, raw.z, raw.w};
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        const int v = (c << 3) + e;
+        const uint32_t p = (w4[e >> 1] >> ((e & 1) * 16)) & 0xFFFFu;
+        if (v < n && (!filter || p >= t16)) f(v, p);
+      }
+    }
+  };
+  float thr = -INFINITY;
+  if (filter) {
+    uint32_t lowkey = 0;
+#pragma unroll
+    for (int pass = 0; pass < 2; ++pass) {
+      zero_hist(hist);
+      __syncthreads();
+      const int shift = pass == 0 ? 8 : 0;
+      for_each_candidate([&](int v, uint32_t p) {
+        if (p == t16) {
+          const uint32_t kk = zkey(zc[v]) & 0xFFFFu;
+          if (pass == 0 || (kk >> 8) == (lowkey >> 8)) atomicAdd(&hist[(kk >> shift) & 0xFFu], 1u);
+        }
+      });
+      __syncthreads();
+      lowkey |= find_bin(hist, need_ab, sm) << shift;
+    }
+    thr = key_to_float((t16 << 16) | lowkey);
+  }
+  float sum = 0.f;
+  int cnt = 0;
+  for_each_candidate([&](int v, uint32_t) {
+    const float z = zc[v];
+    if (z >= thr) {
+      sum += expf(z - m);
+      ++cnt;
+    }
+  });
+  sum = wave_sum(sum);
+  cnt = wave_sum_i32(cnt);
+  if (lane == 0) {
+    sm.fred[wave] = sum;
+    sm.ired[wave] = cnt;
+  }
+  __syncthreads();
+  float S = 0.f;
+  int Cn = 0;
+#pragma unroll
+  for (int w = 0; w < NW; ++w) {
+    S += sm.fred[w];
+    Cn += sm.ired[w];
+  }
+  const float lse_c = m + logf(S);
+  if (tid == 0) {
+    a.thr[R.oidx] = thr;
+    a.lse[R.oidx] = lse_c;
+    a.nkept[R.oidx] = Cn;
+    if (a.flags && !(lse_c == lse_c && fabsf(lse_c) < INFINITY)) atomicOr(a.flags, 1);
+  }
+  if (a.mode == kRowSelectOnly) return;
+  const int j = R.p0 + R.s;
+  const float q_uniform = __fdiv_rn(1.0f, static_cast<float>(n));
+  const uint2 key = seed_key(a.seed);
+  const uint32_t w3 = static_cast<uint32_t>(R.b) << 8;
+  const bool x_ok = R.x >= 0 && R.x < n;
+  out.px = x_ok ? prob(zcx, thr, lse_c) : 0.f;
+  out.qx = R.fresh ? q_uniform : (x_ok ? prob(zpx, R.thr_p, R.lse_p) : 0.f);
+  const uint4 ra = philox4x32_10(make_uint4(0u, static_cast<uint32_t>(j), static_cast<uint32_t>(R.it),
+                                            w3 | kStreamAccept), key);
+  out.accept = __fmul_rn(u01(ra.x), out.qx) <= out.px;
+  out.best = INFINITY;
+  out.best_id = 0x7FFFFFFF;
+  if (!out.accept) {
+    for_each_candidate([&](int v, uint32_t) {
+      const float pv = prob(zc[v], thr, lse_c);
+      if (pv > 0.f) {
+        const float qv = R.fresh ? q_uniform : prob(zp[v], R.thr_p, R.lse_p);
+        const float rv = __fsub_rn(pv, qv);
+        if (rv > 0.f) {
+          const uint4 rr = philox4x32_10(make_uint4(static_cast<uint32_t>(v >> 2), static_cast<uint32_t>(j),
+                                                    static_cast<uint32_t>(R.it), w3 | kStreamResid), key);
+          const uint32_t lanes[4] = {rr.x, rr.y, rr.z, rr.w};
+          const float sc = __fdiv_rn(-logf(u01(lanes[v & 3])), rv);
+          if (sc < out.best || (sc == out.best && v < out.best_id)) {
+            out.best = sc;
+            out.best_id = v;
+          }
+        }
+      }
+    });
+  }
+}
+
+__global__ __launch_bounds__(THREADS) void row_kernel(const RowArgs a, const int P, const int capE) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  __shared__ Small sm;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int n = a.n;
+  const int r = blockIdx.x;
+  const RowRef R = locate_row(a, r);
+  if (!R.active) {
+    if (tid == 0) {
+      a.y[R.widx] = -1;
+      a.k[R.widx] = 1;
+      if (a.px) a.px[R.widx] = 0.f;
+      if (a.qx) a.qx[R.widx] = 0.f;
+      if (a.mode == kRowRing && R.s == 0) a.accept_len[R.b] = 0;   // finished sequence
+    }
+    return;
+  }
+  // the two logits of the draft token: their latency hides behind the selection
+  const bool x_ok = a.mode != kRowSelectOnly && R.x >= 0 && R.x < n;
+  const float zcx = x_ok ? R.zc[R.x] : 0.f;
+  const float zpx = (x_ok && !R.fresh) ? R.zp[R.x] : 0.f;
+  const bool filter = a.top_k > 0 && a.top_k < n;
+
+  RowOut out{};
+  out.accept = true;
+  bool done = false;
+  if (n <= kDirectMaxN) {
+    // ---- the whole row in registers ------------------------------------------------
+    uint32_t* hist = reinterpret_cast<uint32_t*>(smem);
+    const bool vec_ok = (n & 3) == 0;
+    int vid[PER_DIRECT];
+    float zv[PER_DIRECT];
+    bool ok[PER_DIRECT];
+#pragma unroll
+    for (int u = 0; u < PER_DIRECT / 4; ++u) {
+      const int v0 = (tid + u * THREADS) << 2;
+      if (vec_ok && v0 + 3 < n) {
+        const float4 t = *reinterpret_cast<const float4*>(R.zc + v0);
+        zv[u * 4 + 0] = t.x; zv[u * 4 + 1] = t.y; zv[u * 4 + 2] = t.z; zv[u * 4 + 3] = t.w;
+      } else {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) zv[u * 4 + e] = (v0 + e < n) ? R.zc[v0 + e] : 0.f;
+      }
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        vid[u * 4 + e] = v0 + e;
+        ok[u * 4 + e] = v0 + e < n;
+      }
+    }
+    uint32_t* cid = hist + NBINS;
+    finish_regs<PER_DIRECT>(a, R, vid, zv, ok, filter, 0u, zcx, zpx, hist, cid,
+                            reinterpret_cast<float*>(cid + kKeptCap), kKeptCap, sm, out);
+    done = true;
+  } else if (filter && a.cand && P > 0) {
+    // ---- candidates emitted by the slice kernel ----------------------------------
+    uint32_t* hist = reinterpret_cast<uint32_t*>(smem + static_cast<size_t>((n + 7) & ~7) * 2);
+    const uint32_t* cnt_in = a.cand_cnt + static_cast<size_t>(r) * 8;
+    const uint32_t* cut_in = a.cand_cut + static_cast<size_t>(r) * 8;
+    bool fits = true;
+    uint32_t cut_max = 0, total = 0;
+    for (int p = 0; p < P; ++p) {
+      const uint32_t c = cnt_in[p], q = cut_in[p];
+      fits &= c <= static_cast<uint32_t>(capE);
+      total += c;
+      cut_max = q > cut_max ? q : cut_max;
+    }
+    if (fits && total >= static_cast<uint32_t>(a.top_k)) {
+      const uint2* src = a.cand + static_cast<size_t>(r) * kListCap;
+      int vid[PER_LIST];
+      float zv[PER_LIST];
+      bool ok[PER_LIST];
+#pragma unroll
+      for (int e = 0; e < PER_LIST; ++e) {
+        const int i = tid + e * THREADS;
+        const int p = i / capE, o = i - p * capE;
+        ok[e] = p < P && static_cast<uint32_t>(o) < cnt_in[p];
+        const uint2 t = ok[e] ? src[i] : make_uint2(0u, 0u);
+        vid[e] = static_cast<int>(t.x);
+        zv[e] = __uint_as_float(t.y);
+      }
+      const int ccap = min(kKeptCap, static_cast<int>(static_cast<size_t>((n + 7) & ~7) * 2 / 8));
+      done = finish_regs<PER_LIST>(a, R, vid, zv, ok, true, cut_max, zcx, zpx, hist,
+                                   reinterpret_cast<uint32_t*>(smem), reinterpret_cast<float*>(smem) + ccap,
+                                   ccap, sm, out);
+    }
+  }
+  if (!done) full_path(a, R, smem, zcx, zpx, sm, out);
+  if (a.mode == kRowSelectOnly) return;
+
   // ---- winner of the race (lexicographic (score, id) minimum) -------------------
-  int y_out = x;
+  int y_out = R.x;
   int k_out = 1;
-  if (!accept) {
+  if (!out.accept) {
+    float best = out.best;
+    int best_id = out.best_id;
 #pragma unroll
     for (int o = 32; o > 0; o >>= 1) {
       const float os = __shfl_xor(best, o, kWave);
@@ -565,14 +909,15 @@ __global__ __launch_bounds__(THREADS) void row_kernel(const RowArgs a) {
     }
   }
   if (tid == 0) {
-    a.y[widx] = y_out;
-    a.k[widx] = static_cast<uint8_t>(k_out);
-    if (a.px) a.px[widx] = px;
-    if (a.qx) a.qx[widx] = qx;
+    a.y[R.widx] = y_out;
+    a.k[R.widx] = static_cast<uint8_t>(k_out);
+    if (a.px) a.px[R.widx] = out.px;
+    if (a.qx) a.qx[R.widx] = out.qx;
   }
   if (a.mode != kRowRing) return;
 
   // ---- last workgroup of the sequence: first rejection, emit, slide -----------
+  const int b = R.b, p0 = R.p0, live = R.live;
   if (tid == 0) {
     __threadfence();
     sm.last = atomicAdd(&a.ticket[b], 1) == live - 1;
@@ -605,21 +950,47 @@ __global__ __launch_bounds__(THREADS) void row_kernel(const RowArgs a) {
   if (tid == 0) {
     a.accept_len[b] = acc;
     a.pos[b] = p0 + acc;
-    a.iter[b] = it + 1;
+    a.iter[b] = R.it + 1;
     a.verified[b] += live;
     a.ticket[b] = 0;
   }
 }
 
-}  // namespace
-
-size_t row_kernel_lds_bytes(int n) {
+size_t lds_bytes_for(int n) {
+  if (n <= kDirectMaxN) return NBINS * sizeof(uint32_t) + kKeptCap * 8;
   return static_cast<size_t>((n + 7) & ~7) * 2 + NBINS * sizeof(uint32_t) + kListCap * sizeof(uint16_t);
 }
 
-hipError_t launch_row(const RowArgs& a, hipStream_t s) {
-  if (a.rows <= 0) return hipSuccess;
-  const size_t lds = row_kernel_lds_bytes(a.n);
+inline size_t small_block(int rows) { return (static_cast<size_t>(rows) * 8 * 4 + 255) / 256 * 256; }
+
+}  // namespace
+
+size_t row_candidate_bytes(int rows) {
+  // per row: kListCap (id, logit) pairs, 8 slice counts, 8 slice cuts
+  return static_cast<size_t>(rows) * kListCap * sizeof(uint2) + 2 * small_block(rows);
+}
+
+hipError_t launch_row(const RowArgs& a_in, hipStream_t s) {
+  if (a_in.rows <= 0) return hipSuccess;
+  RowArgs a = a_in;
+  const bool filter = a.top_k > 0 && a.top_k < a.n;
+  int P = 0, capE = 0;
+  a.cand = nullptr;
+  if (a.n > kDirectMaxN && filter && a.cand_base && a.top_k <= kListCap / 2) {
+    P = (a.n + kSliceMax - 1) / kSliceMax;                     // <= 8 for n <= 65536
+    capE = kListCap / P;
+    int rank = (2 * a.top_k + P - 1) / P;
+    rank = rank < 64 ? 64 : rank;
+    if (rank > capE * 4 / 5) rank = capE * 4 / 5;
+    char* base = static_cast<char*>(a.cand_base);
+    const size_t pairs = static_cast<size_t>(a.rows) * kListCap * sizeof(uint2);
+    a.cand = reinterpret_cast<uint2*>(base);
+    a.cand_cnt = reinterpret_cast<uint32_t*>(base + pairs);
+    a.cand_cut = reinterpret_cast<uint32_t*>(base + pairs + small_block(a.rows));
+    hipLaunchKernelGGL(slice_kernel, dim3(a.rows * P), dim3(THREADS), 0, s, a, P, capE, rank);
+    if (hipError_t e = hipGetLastError(); e != hipSuccess) return e;
+  }
+  const size_t lds = lds_bytes_for(a.n);
   static size_t configured = 0;          // grows monotonically; benign if raced (idempotent call)
   if (lds > configured) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(row_kernel),
@@ -628,7 +999,7 @@ hipError_t launch_row(const RowArgs& a, hipStream_t s) {
     if (e != hipSuccess) return e;
     configured = lds;
   }
-  hipLaunchKernelGGL(row_kernel, dim3(a.rows), dim3(THREADS), lds, s, a);
+  hipLaunchKernelGGL(row_kernel, dim3(a.rows), dim3(THREADS), lds, s, a, P, capE);
   return hipGetLastError();
 }
 

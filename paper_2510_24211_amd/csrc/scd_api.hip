@@ -67,10 +67,14 @@ Layout make_layout(const scd_config& c) {
 }
 
 // Workspace: thresholds / normalisers / kept counts of the two logit arrays of
-// a stand-alone scd_couple_draft call.
-size_t workspace_need(const scd_config& c) {
+// a stand-alone scd_couple_draft call ...
+size_t small_need(const scd_config& c) {
   const size_t rows = static_cast<size_t>(c.B) * c.L;
   return 6 * align_up(4 * rows);
+}
+// ... followed by the per-row candidate scratch of the slice kernel.
+size_t workspace_need(const scd_config& c) {
+  return small_need(c) + align_up(scd::row_candidate_bytes(c.B * c.L));
 }
 
 }  // namespace
@@ -125,6 +129,7 @@ int run_tail(scd_ctx* c, void* st) {
     ra.rows = c->cfg.B * c->cfg.L;
     ra.B = c->cfg.B; ra.L = c->cfg.L; ra.N = c->cfg.N; ra.n = c->n; ra.top_k = c->cfg.top_k;
     ra.v_lo = c->cfg.v_lo; ra.seed = c->cfg.seed;
+    ra.cand_base = static_cast<char*>(c->ws) + small_need(c->cfg);
     return hip_rc(scd::launch_row(ra, c->stream));
   }
   // rows too long for the LDS-resident kernel: select -> MRS -> commit
@@ -260,6 +265,7 @@ int scd_select(scd_ctx* c, const float* d_z, int32_t rows, float* d_thr, float* 
     ra.z_cur = d_z; ra.thr = d_thr; ra.lse = d_lse; ra.nkept = d_nkept;
     ra.rows = rows;
     ra.B = c->cfg.B; ra.L = c->cfg.L; ra.N = c->cfg.N; ra.n = c->n; ra.top_k = c->cfg.top_k;
+    if (rows <= c->cfg.B * c->cfg.L) ra.cand_base = static_cast<char*>(c->ws) + small_need(c->cfg);
     return hip_rc(scd::launch_row(ra, c->stream));
   }
   scd::SelectArgs a{};
@@ -296,6 +302,7 @@ int scd_couple_draft(scd_ctx* c, const float* d_z_cur, const float* d_z_prev, co
     ra.rows = rows;
     ra.B = c->cfg.B; ra.L = c->cfg.L; ra.N = c->cfg.N; ra.n = c->n; ra.top_k = c->cfg.top_k;
     ra.v_lo = c->cfg.v_lo; ra.seed = c->cfg.seed;
+    ra.cand_base = static_cast<char*>(c->ws) + small_need(c->cfg);
     return hip_rc(scd::launch_row(ra, c->stream));
   }
   if (int rc = scd_select(c, d_z_cur, rows, thr_c, lse_c, nk_c); rc != SCD_OK) return rc;

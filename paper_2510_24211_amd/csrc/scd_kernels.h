@@ -94,8 +94,14 @@ struct RowArgs {
   int rows;              // select-only: rows; else B*L
   int B, L, N, n, top_k, v_lo;
   uint64_t seed;
+  // scratch for the slice kernel (rows longer than 8192 ids): row_candidate_bytes(rows)
+  // bytes of device memory, 256-byte aligned, or null (then rows are processed whole)
+  void* cand_base;
+  uint2* cand;           // set by launch_row
+  uint32_t* cand_cnt;    // set by launch_row
+  uint32_t* cand_cut;    // set by launch_row
 };
-size_t row_kernel_lds_bytes(int n);
+size_t row_candidate_bytes(int rows);
 hipError_t launch_row(const RowArgs& a, hipStream_t s);
 
 // ---- first rejection, emit, slide -----------------------------------------
