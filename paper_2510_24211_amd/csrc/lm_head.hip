@@ -14,17 +14,22 @@
 //     ahead in registers, parks a tile in a wavefront-PRIVATE LDS region (pitch
 //     144 bytes against bank conflicts) and reads it back in the operand layout
 //     of v_mfma_f32_32x32x16_bf16 (lane l: row l%32, k-group l/32, 8 consecutive
-//     k).  Private staging needs no workgroup barrier, so the four wavefronts of
-//     a workgroup drift apart and the W stream never drains.
+//     k).  Private staging needs no workgroup barrier, so the wavefronts of a
+//     workgroup drift apart and the W stream never drains.
+//   * The NW wavefronts of a workgroup take NW x 32 neighbouring columns and
+//     SHARE the h tile through LDS (double buffered, loaded two tiles ahead, one
+//     barrier per h tile): h comes out of L2 once per workgroup, not per wavefront.
 //   * The accumulators of a wavefront are RBW "row blocks" x C tiles: a row block
 //     is 32 window positions of one sequence, its cond and uncond tiles live in
 //     the SAME lanes, so the guidance mix needs no data movement.
-//   * KS = 1 (wide vocabularies): the 4 wavefronts take 4 x 32 neighbouring
-//     columns and SHARE the h tile through LDS (double buffered, one barrier per
-//     h tile).  KS = 4 (narrow vocabularies, too few column tiles to fill 256
-//     CUs): the 4 wavefronts take the same 32 columns and a quarter of k each,
-//     stage h privately too, and their partial sums are added in a fixed order
-//     through LDS at the end (deterministic).
+//   * Every workgroup walks k cyclically from its own starting tile: rows of W
+//     are d*2 bytes apart, and without the rotation all wavefronts of the chip
+//     ask for the same address bits at the same time and camp on a few channels.
+//   * Narrow vocabularies give too few 128-column tiles to fill 256 CUs.  They use
+//     lm_head_splitk_kernel: a workgroup owns 32 columns, its KS wavefronts take a
+//     1/KS part of k each, stage their own h tiles privately as well (no barrier in
+//     the loop), and their partial sums are added in wavefront order through LDS at
+//     the end (a fixed order: deterministic).
 #include "scd_kernels.h"
 
 namespace scd {
@@ -32,260 +37,38 @@ namespace {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
+// 16-byte register value; a native vector (the HIP struct type is copied with memcpy,
+// which keeps arrays of it in scratch memory)
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int BK = 64;          // k elements per W tile (128 bytes per row)
 constexpr int PITCH = BK + 8;   // LDS row pitch in bf16 elements (144 bytes)
+
 __device__ __forceinline__ void compiler_fence() { asm volatile("" ::: "memory"); }
 
-template <int RBW, int C, int KS, int NWV>
+template <int RBW, int C, int NWV>
 struct Cfg {
-  static constexpr int NW = KS == 1 ? NWV : KS;   // wavefronts per workgroup
+  static constexpr int NW = NWV;                  // wavefronts per workgroup
   static constexpr int THREADS = NW * 64;
   static constexpr int NBLK = RBW * C;            // accumulator tiles per wavefront
   static constexpr int HROWS = NBLK * 32;         // h rows per tile
-  // W tiles in flight per wavefront (registers)
-  static constexpr int D = KS == 1 ? 4 : (KS == 8 ? 2 : 4);
+  static constexpr int D = 4;                     // W tiles in flight per wavefront (registers)
   static constexpr int DH = 2;                    // h tiles in flight (registers)
-  static constexpr int HT = (KS == 1 && NBLK <= 2) ? 2 : 1;   // W tiles per shared h tile
+  static constexpr int HT = NBLK <= 2 ? 2 : 1;    // W tiles per shared h tile
   static constexpr int BKH = BK * HT;
   static constexpr int PITCH_H = BKH + 8;
-  static constexpr int BN = KS == 1 ? NW * 32 : 32;   // columns per workgroup
-  static constexpr int W_LDS = NW * 32 * PITCH;                     // elements
-  static constexpr int H_LDS = KS == 1 ? 2 * HROWS * PITCH_H : NW * HROWS * PITCH;
-  static constexpr int RED_BYTES = KS == 1 ? 0 : NW * NBLK * 16 * 64 * 4;
-  static constexpr int STAGE_BYTES = (W_LDS + H_LDS) * 2;
-  static constexpr int LDS_BYTES = STAGE_BYTES > RED_BYTES ? STAGE_BYTES : RED_BYTES;
+  static constexpr int BN = NW * 32;              // columns per workgroup
+  static constexpr int W_LDS = NW * 32 * PITCH;   // elements
+  static constexpr int H_LDS = 2 * HROWS * PITCH_H;
+  static constexpr int LDS_BYTES = (W_LDS + H_LDS) * 2;
 };
 
-template <int RBW, int C, int KS, int NWV>
-__global__ __launch_bounds__((Cfg<RBW, C, KS, NWV>::THREADS)) void lm_head_kernel(const LmHeadArgs a, const int nLb,
-                                                          const int nRB, const int VT,
-                                                          const int MT) {
-  using K = Cfg<RBW, C, KS, NWV>;
-  constexpr int NBLK = K::NBLK, HROWS = K::HROWS, D = K::D, DH = K::DH, HT = K::HT;
-  constexpr int NWAVE = K::NW, THREADS = K::THREADS;
-  __shared__ __attribute__((aligned(16))) unsigned char lds_raw[K::LDS_BYTES];
-  uint16_t* const Ws_all = reinterpret_cast<uint16_t*>(lds_raw);
-  uint16_t* const Hs_all = Ws_all + K::W_LDS;
-
-  // Workgroups with consecutive ids land on different XCDs (round robin over
-  // 8); the MT row-block tiles that share one slab of W get ids 8 apart, i.e.
-  // the same XCD and the same L2.
-  const int id = blockIdx.x;
-  const int vt = (id / (8 * MT)) * 8 + (id % 8);
-  const int mt = (id / 8) % MT;
-  if (vt >= VT) return;
-  const int rb0 = mt * RBW;
-
-  const int tid = threadIdx.x;
-  const int wave = tid >> 6;
-  const int lane = tid & 63;
-  const int ln = lane & 31;     // row (A) / column (B) inside a 32x32 tile
-  const int lg = lane >> 5;     // k-group
-  const int chunk = lane & 7;   // 16-byte chunk inside a 128-byte row segment
-  const int lrow = lane >> 3;   // 0..7
-
-  const int d = a.d;
-  const int KT = (d + BK - 1) / BK;
-  // this wavefront's columns and k-tiles
-  const int v0 = vt * K::BN + (KS == 1 ? wave * 32 : 0);
-  const int ktq = KS == 1 ? KT : (KT + NWAVE - 1) / NWAVE;
-  const int kt_begin = KS == 1 ? 0 : wave * ktq;
-  const int kt_end = KS == 1 ? KT : min(KT, kt_begin + ktq);
-  const int ntiles = max(0, kt_end - kt_begin);
-  const int ntiles_pad = (ntiles + D - 1) / D * D;
-  // Every workgroup walks k from a different starting tile (cyclically).  Rows of W
-  // are d*2 bytes apart, so without the rotation all wavefronts of the chip would ask
-  // for the same address bits (mod the row pitch) at the same time and camp on a few
-  // memory channels.  An odd multiplier spreads the starts over every tile offset.
-  const int rot = ntiles_pad > 0 ? (vt * 5 + (KS == 1 ? 0 : wave * 3)) % ntiles_pad : 0;
-  auto ktile = [&](int t) {          // logical tile t of this wavefront -> k-tile index, -1 if none
-    if (t >= ntiles_pad) return -1;
-    int r = t + rot;
-    if (r >= ntiles_pad) r -= ntiles_pad;
-    return r < ntiles ? kt_begin + r : -1;
-  };
-
-  uint16_t* const Ws = Ws_all + wave * 32 * PITCH;          // private W staging
-
-  // ---- W: coalesced private loads, D tiles ahead -----------------------------------
-  const uint16_t* wsrc[4];
-  bool wok[4];
-#pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    const int v = v0 + lrow + 8 * i;
-    wok[i] = v < a.n;
-    wsrc[i] = a.W + static_cast<size_t>(wok[i] ? v : 0) * d;
-  }
-  uint4 wreg[D][4];
-  auto wload = [&](int slot, int t) {       // logical tile index t
-    const int kt = ktile(t);
-    const int k = kt * BK + chunk * 8;
-    const bool kok = kt >= 0 && k < d;
-#pragma unroll
-    for (int i = 0; i < 4; ++i)
-      wreg[slot][i] = (wok[i] && kok) ? *reinterpret_cast<const uint4*>(wsrc[i] + k)
-                                      : make_uint4(0, 0, 0, 0);
-  };
-  auto wstore = [&](int slot) {
-#pragma unroll
-    for (int i = 0; i < 4; ++i)
-      *reinterpret_cast<uint4*>(&Ws[(lrow + 8 * i) * PITCH + chunk * 8]) = wreg[slot][i];
-  };
-
-  // ---- h rows -----------------------------------------------------------------------
-  auto hrow_ptr = [&](int rr, bool& ok) -> const uint16_t* {   // rr = tile row 0..HROWS-1
-    const int blk = rr >> 5, r = rr & 31;
-    const int rb = rb0 + blk / C, c = blk % C;
-    const int b = rb / nLb, s = (rb % nLb) * 32 + r;
-    ok = rb < nRB && s < a.L;
-    return a.h + (ok ? (static_cast<size_t>(b * C + c) * a.L + s) * d : 0);
-  };
-
-  f32x16 acc[NBLK];
-#pragma unroll
-  for (int i = 0; i < NBLK; ++i)
-#pragma unroll
-    for (int j = 0; j < 16; ++j) acc[i][j] = 0.f;
-
-  // MFMAs of one W tile; Hs_tile points at the h rows, column offset koff, row pitch hp
-  auto compute = [&](const uint16_t* Hs_tile, int hp, int koff) {
-#pragma unroll
-    for (int kk = 0; kk < BK / 16; ++kk) {
-      const uint4 braw = *reinterpret_cast<const uint4*>(&Ws[ln * PITCH + kk * 16 + lg * 8]);
-      const bf16x8 bfrag = __builtin_bit_cast(bf16x8, braw);
-#pragma unroll
-      for (int i = 0; i < NBLK; ++i) {
-        const uint4 araw =
-            *reinterpret_cast<const uint4*>(&Hs_tile[(i * 32 + ln) * hp + koff + kk * 16 + lg * 8]);
-        acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, araw), bfrag,
-                                                         acc[i], 0, 0, 0);
-      }
-    }
-  };
-
-  if constexpr (KS == 1) {
-    // ======== shared h tile (BKH = HT * 64 wide), double buffered =====================
-    constexpr int CH = K::BKH / 8;                 // 16-byte chunks per h row
-    constexpr int RPP = THREADS / CH;              // rows covered per pass of the workgroup
-    constexpr int HL = HROWS / RPP;                // loads per thread per h tile
-    const int hchunk = tid % CH, hr0 = tid / CH;
-    const uint16_t* hsrc[HL];
-    bool hok[HL];
-#pragma unroll
-    for (int i = 0; i < HL; ++i) hsrc[i] = hrow_ptr(hr0 + RPP * i, hok[i]);
-    uint4 hreg[DH][HL];
-    // logical h tile st = logical W tiles st*HT .. st*HT+HT-1; after the rotation these
-    // need not be neighbours in k (wrap-around), so every 64-wide part is placed on its own
-    constexpr int CHW = BK / 8;            // 16-byte chunks per W tile width
-    auto hload = [&](int slot, int st) {
-      const int kt = ktile(st * HT + hchunk / CHW);
-      const int k = kt * BK + (hchunk % CHW) * 8;
-      const bool kok = kt >= 0 && k < d;
-#pragma unroll
-      for (int i = 0; i < HL; ++i)
-        hreg[slot][i] = (hok[i] && kok) ? *reinterpret_cast<const uint4*>(hsrc[i] + k)
-                                        : make_uint4(0, 0, 0, 0);
-    };
-    auto hstore = [&](int slot, int buf) {
-      uint16_t* dst = Hs_all + buf * HROWS * K::PITCH_H;
-#pragma unroll
-      for (int i = 0; i < HL; ++i)
-        *reinterpret_cast<uint4*>(&dst[(hr0 + RPP * i) * K::PITCH_H + hchunk * 8]) = hreg[slot][i];
-    };
-    // h tile st is loaded into register stage st % 2 two h tiles ahead, moved to LDS
-    // buffer st % 2 at the end of h tile st - 1, and consumed during h tile st.
-    static_assert(D % (2 * HT) == 0, "register stages of h must be static in the unrolled body");
-#pragma unroll
-    for (int j = 0; j < D; ++j) wload(j, j);
-    hload(0, 0);
-    hload(1, 1);
-    hstore(0, 0);
-    __syncthreads();
-    for (int t0 = 0; t0 < ntiles_pad; t0 += D) {
-#pragma unroll
-      for (int j = 0; j < D; ++j) {
-        const int t = t0 + j;
-        const int st = t / HT;
-        const int stage = (j / HT) & 1;            // == st & 1 because t0 / HT is even
-        compiler_fence();
-        wstore(j);
-        wload(j, t + D);
-        compiler_fence();
-        compute(Hs_all + stage * HROWS * K::PITCH_H, K::PITCH_H, (j % HT) * BK);
-        compiler_fence();
-        if (j % HT == HT - 1) {
-          hstore(stage ^ 1, stage ^ 1);            // h tile st + 1 -> the other LDS buffer
-          hload(stage, st + 2);                    // h tile st + 2 -> the register stage just freed
-          __syncthreads();
-        }
-      }
-    }
-  } else {
-    // ======== split k: everything private to the wavefront, no barrier in the loop =====
-    constexpr int HL = HROWS / 8;                  // loads per lane per h tile
-    uint16_t* const Hs = Hs_all + wave * HROWS * PITCH;
-    const uint16_t* hsrc[HL];
-    bool hok[HL];
-#pragma unroll
-    for (int i = 0; i < HL; ++i) hsrc[i] = hrow_ptr(lrow + 8 * i, hok[i]);
-    uint4 hreg[DH][HL];
-    auto hload = [&](int slot, int t) {
-      const int kt = ktile(t);
-      const int k = kt * BK + chunk * 8;
-      const bool kok = kt >= 0 && k < d;
-#pragma unroll
-      for (int i = 0; i < HL; ++i)
-        hreg[slot][i] = (hok[i] && kok) ? *reinterpret_cast<const uint4*>(hsrc[i] + k)
-                                        : make_uint4(0, 0, 0, 0);
-    };
-    auto hstore = [&](int slot) {
-#pragma unroll
-      for (int i = 0; i < HL; ++i)
-        *reinterpret_cast<uint4*>(&Hs[(lrow + 8 * i) * PITCH + chunk * 8]) = hreg[slot][i];
-    };
-    static_assert(D % DH == 0, "register stages of h must be static in the unrolled body");
-#pragma unroll
-    for (int j = 0; j < D; ++j) wload(j, j);
-#pragma unroll
-    for (int j = 0; j < DH; ++j) hload(j, j);
-    for (int t0 = 0; t0 < ntiles_pad; t0 += D) {
-#pragma unroll
-      for (int j = 0; j < D; ++j) {
-        compiler_fence();
-        wstore(j);
-        hstore(j % DH);
-        wload(j, t0 + j + D);
-        hload(j % DH, t0 + j + DH);
-        compiler_fence();
-        compute(Hs, PITCH, 0);
-        compiler_fence();
-      }
-    }
-    if constexpr (KS > 1) {
-    // fixed-order sum of the partial accumulators through LDS
-    __syncthreads();
-    float* red = reinterpret_cast<float*>(lds_raw);
-#pragma unroll
-    for (int i = 0; i < NBLK; ++i)
-#pragma unroll
-      for (int j = 0; j < 16; ++j) red[((wave * NBLK + i) * 16 + j) * 64 + lane] = acc[i][j];
-    __syncthreads();
-#pragma unroll
-    for (int i = 0; i < NBLK; ++i)
-#pragma unroll
-      for (int j = 0; j < 16; ++j) {
-        float sum = red[((0 * NBLK + i) * 16 + j) * 64 + lane];
-#pragma unroll
-        for (int w = 1; w < NWAVE; ++w) sum += red[((w * NBLK + i) * 16 + j) * 64 + lane];
-        acc[i][j] = sum;
-      }
-    }
-  }
-
-  // ---- epilogue.  Accumulator element j of lane (ln, lg) is row (j/4)*8 + lg*4 + j%4,
-  // column ln of the 32x32 tile.  With split k every wavefront holds the full sums and
-  // stores the accumulator elements j with j % (number of wavefronts) == its index.
+// Epilogue for the accumulator elements j = j0, j0 + jstep, ... < j1.  Element j of lane
+// (ln, lg) is row (j/4)*8 + lg*4 + j%4, column ln of the 32x32 tile.
+template <int RBW, int C>
+__device__ __forceinline__ void epilogue(const LmHeadArgs& a, const f32x16 (&acc)[RBW * C], int nLb,
+                                         int nRB, int rb0, int v0, int ln, int lg, int j0, int j1,
+                                         int jstep) {
   const int v = v0 + ln;
   if (v >= a.n) return;
 #pragma unroll
@@ -303,7 +86,7 @@ __global__ __launch_bounds__((Cfg<RBW, C, KS, NWV>::THREADS)) void lm_head_kerne
     if (a.iter) zb += static_cast<size_t>(a.iter[b] & 1) * a.parity_stride;
 #pragma unroll
     for (int j = 0; j < 16; ++j) {
-      if (KS > 1 && (j % NWAVE) != wave) continue;
+      if (j < j0 || j >= j1 || (j - j0) % jstep != 0) continue;
       const int s = sbase + (j >> 2) * 8 + lg * 4 + (j & 3);
       if (s >= live) continue;
       float z;
@@ -321,17 +104,343 @@ __global__ __launch_bounds__((Cfg<RBW, C, KS, NWV>::THREADS)) void lm_head_kerne
   }
 }
 
-template <int RBW, int C, int KS, int NWV = 4>
-hipError_t launch_t(const LmHeadArgs& a, hipStream_t s) {
-  using K = Cfg<RBW, C, KS, NWV>;
+template <int RBW, int C, int NWV>
+__global__ __launch_bounds__((Cfg<RBW, C, NWV>::THREADS)) void lm_head_kernel(
+    const LmHeadArgs a, const int nLb, const int nRB, const int VT, const int MT) {
+  using K = Cfg<RBW, C, NWV>;
+  constexpr int NBLK = K::NBLK, HROWS = K::HROWS, D = K::D, DH = K::DH, HT = K::HT;
+  constexpr int THREADS = K::THREADS;
+  __shared__ __attribute__((aligned(16))) unsigned char lds_raw[K::LDS_BYTES];
+  uint16_t* const Ws_all = reinterpret_cast<uint16_t*>(lds_raw);
+  uint16_t* const Hs_all = Ws_all + K::W_LDS;
+
+  // Workgroups with consecutive ids land on different XCDs (round robin over 8).  The
+  // MT row-block tiles that share one slab of W get ids 8 apart, i.e. the same XCD and
+  // the same L2.
+  const int id = blockIdx.x;
+  const int vt = (id / (8 * MT)) * 8 + (id % 8);
+  const int mt = (id / 8) % MT;
+  if (vt >= VT) return;
+  const int rb0 = mt * RBW;
+
+  const int tid = threadIdx.x;
+  const int wave = tid >> 6;
+  const int lane = tid & 63;
+  const int ln = lane & 31;     // row (A) / column (B) inside a 32x32 tile
+  const int lg = lane >> 5;     // k-group
+  const int chunk = lane & 7;   // 16-byte chunk inside a 128-byte row segment
+  const int lrow = lane >> 3;   // 0..7
+
+  const int d = a.d;
+  const int KT = (d + BK - 1) / BK;
+  const int v0 = vt * K::BN + wave * 32;
+  const int ntiles = KT;
+  const int ntiles_pad = (ntiles + D - 1) / D * D;
+  const int rot = (vt * 5) % ntiles_pad;
+  // logical tile t -> k-tile index; `valid` is false for the padding tiles of the rotation
+  // and for prefetches past the end.  Loads are NEVER predicated (a predicated load is a
+  // branch, and branches keep the scheduler from batching the loads): an invalid tile reads
+  // tile 0 of W (finite weights) against an h tile that is forced to zero.
+  auto ktile = [&](int t, bool& valid) {
+    int r = t + rot;
+    if (r >= ntiles_pad) r -= ntiles_pad;
+    valid = t < ntiles_pad && r < ntiles;
+    return valid ? r : 0;
+  };
+
+  uint16_t* const Ws = Ws_all + wave * 32 * PITCH;          // private W staging
+
+  // ---- W: coalesced private loads, D tiles ahead -----------------------------------
+  // 32-bit byte offsets from the (uniform) base; rows past the end are clamped to the last
+  // row (their columns are never stored), k past the end to the last 16-byte chunk.
+  const char* const Wb = reinterpret_cast<const char*>(a.W);
+  uint32_t woff[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+    woff[i] = static_cast<uint32_t>(min(v0 + lrow + 8 * i, a.n - 1)) * static_cast<uint32_t>(d) * 2u;
+  const uint32_t kclamp = static_cast<uint32_t>(d - 8) * 2u;
+  u32x4 wreg[D][4];
+  auto wload = [&](int slot, int t) {       // logical tile index t
+    bool valid;
+    const int kt = ktile(t, valid);
+    const uint32_t kb = min(static_cast<uint32_t>(kt * BK + chunk * 8) * 2u, kclamp);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) wreg[slot][i] = *reinterpret_cast<const u32x4*>(Wb + (woff[i] + kb));
+  };
+  auto wstore = [&](int slot) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+      *reinterpret_cast<u32x4*>(&Ws[(lrow + 8 * i) * PITCH + chunk * 8]) = wreg[slot][i];
+  };
+
+  // ---- h: shared tile, BKH = HT * 64 wide --------------------------------------------
+  constexpr int CH = K::BKH / 8;                 // 16-byte chunks per h row
+  constexpr int CHW = BK / 8;                    // 16-byte chunks per W tile width
+  constexpr int RPP = THREADS / CH;              // rows covered per pass of the workgroup
+  constexpr int HL = HROWS / RPP;                // loads per thread per h tile
+  static_assert(HROWS % RPP == 0, "h tile must divide over the workgroup");
+  const int hchunk = tid % CH, hr0 = tid / CH;
+  const char* const Hb = reinterpret_cast<const char*>(a.h);
+  uint32_t hoff[HL];
+  bool hok[HL];
+#pragma unroll
+  for (int i = 0; i < HL; ++i) {
+    const int rr = hr0 + RPP * i;                // tile row 0..HROWS-1
+    const int blk = rr >> 5, r = rr & 31;
+    const int rb = rb0 + blk / C, c = blk % C;
+    const int b = rb / nLb, s = (rb % nLb) * 32 + r;
+    hok[i] = rb < nRB && s < a.L;
+    hoff[i] = hok[i] ? static_cast<uint32_t>((b * C + c) * a.L + s) * static_cast<uint32_t>(d) * 2u : 0u;
+  }
+  u32x4 hreg[DH][HL];
+  bool hkok[DH];
+  // logical h tile st = logical W tiles st*HT .. st*HT+HT-1; after the rotation these
+  // need not be neighbours in k (wrap-around), so every 64-wide part is placed on its own.
+  // Loaded unconditionally from a clamped address, then zeroed where the row or k is not real.
+  auto hload = [&](int slot, int st) {
+    bool valid;
+    const int kt = ktile(st * HT + hchunk / CHW, valid);
+    const int k = kt * BK + (hchunk % CHW) * 8;
+    const bool kok = valid && k < d;
+    const uint32_t kb = min(static_cast<uint32_t>(k) * 2u, kclamp);
+#pragma unroll
+    for (int i = 0; i < HL; ++i) hreg[slot][i] = *reinterpret_cast<const u32x4*>(Hb + (hoff[i] + kb));
+    hkok[slot] = kok;
+  };
+  // the zeroing waits for the load, so it happens here, when the tile moves to LDS
+  auto hstore = [&](int slot, int buf) {
+    uint16_t* dst = Hs_all + buf * HROWS * K::PITCH_H;
+#pragma unroll
+    for (int i = 0; i < HL; ++i) {
+      const u32x4 t4 = hreg[slot][i];
+      const bool keep = hok[i] && hkok[slot];
+      *reinterpret_cast<u32x4*>(&dst[(hr0 + RPP * i) * K::PITCH_H + hchunk * 8]) =
+          (keep ? t4 : u32x4{0u, 0u, 0u, 0u});
+    }
+  };
+
+  f32x16 acc[NBLK];
+#pragma unroll
+  for (int i = 0; i < NBLK; ++i)
+#pragma unroll
+    for (int j = 0; j < 16; ++j) acc[i][j] = 0.f;
+
+  // MFMAs of one W tile against h tile `Hs_tile` at column offset koff
+  auto compute = [&](const uint16_t* Hs_tile, int koff) {
+#pragma unroll
+    for (int kk = 0; kk < BK / 16; ++kk) {
+      const u32x4 braw = *reinterpret_cast<const u32x4*>(&Ws[ln * PITCH + kk * 16 + lg * 8]);
+      const bf16x8 bfrag = __builtin_bit_cast(bf16x8, braw);
+#pragma unroll
+      for (int i = 0; i < NBLK; ++i) {
+        const u32x4 araw = *reinterpret_cast<const u32x4*>(
+            &Hs_tile[(i * 32 + ln) * K::PITCH_H + koff + kk * 16 + lg * 8]);
+        acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, araw), bfrag,
+                                                         acc[i], 0, 0, 0);
+      }
+    }
+  };
+
+  // h tile st is loaded into register stage st % 2 two h tiles ahead, moved to LDS buffer
+  // st % 2 at the end of h tile st - 1, and consumed during h tile st.
+  static_assert(D % (2 * HT) == 0, "register stages of h must be static in the unrolled body");
+#pragma unroll
+  for (int j = 0; j < D; ++j) wload(j, j);
+  hload(0, 0);
+  hload(1, 1);
+  hstore(0, 0);
+  __syncthreads();
+  for (int t0 = 0; t0 < ntiles_pad; t0 += D) {
+#pragma unroll
+    for (int j = 0; j < D; ++j) {
+      const int t = t0 + j;
+      const int st = t / HT;
+      const int stage = (j / HT) & 1;            // == st & 1 because t0 / HT is even
+      compiler_fence();
+      wstore(j);
+      wload(j, t + D);
+      compiler_fence();
+      compute(Hs_all + stage * HROWS * K::PITCH_H, (j % HT) * BK);
+      compiler_fence();
+      if (j % HT == HT - 1) {
+        hstore(stage ^ 1, stage ^ 1);            // h tile st + 1 -> the other LDS buffer
+        hload(stage, st + 2);                    // h tile st + 2 -> the register stage just freed
+        __syncthreads();
+      }
+    }
+  }
+
+  epilogue<RBW, C>(a, acc, nLb, nRB, rb0, v0, ln, lg, 0, 16, 1);
+}
+
+// ---- narrow vocabularies: k split over the wavefronts of a workgroup ---------------------
+template <int RBW, int C, int KS>
+struct SplitCfg {
+  static constexpr int NW = KS;
+  static constexpr int THREADS = NW * 64;
+  static constexpr int NBLK = RBW * C;
+  static constexpr int HROWS = NBLK * 32;
+  static constexpr int D = KS == 8 ? 2 : 4;       // W tiles in flight per wavefront
+  static constexpr int DH = 2;                    // h tiles in flight per wavefront
+  static constexpr int STAGE_BYTES = NW * (32 + HROWS) * PITCH * 2;
+  static constexpr int RED_BYTES = NW * NBLK * 16 * 64 * 4;
+  static constexpr int LDS_BYTES = STAGE_BYTES > RED_BYTES ? STAGE_BYTES : RED_BYTES;
+};
+
+template <int RBW, int C, int KS>
+__global__ __launch_bounds__((SplitCfg<RBW, C, KS>::THREADS)) void lm_head_splitk_kernel(
+    const LmHeadArgs a, const int nLb, const int nRB, const int VT, const int MT) {
+  using K = SplitCfg<RBW, C, KS>;
+  constexpr int NBLK = K::NBLK, HROWS = K::HROWS, D = K::D, DH = K::DH, NWAVE = K::NW;
+  __shared__ __attribute__((aligned(16))) unsigned char lds_raw[K::LDS_BYTES];
+  const int id = blockIdx.x;
+  const int vt = (id / (8 * MT)) * 8 + (id % 8);
+  const int mt = (id / 8) % MT;
+  if (vt >= VT) return;
+  const int rb0 = mt * RBW;
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  const int ln = lane & 31, lg = lane >> 5, chunk = lane & 7, lrow = lane >> 3;
+  const int d = a.d;
+  const int KT = (d + BK - 1) / BK;
+  const int v0 = vt * 32;
+  const int ktq = (KT + NWAVE - 1) / NWAVE;
+  const int kt_begin = wave * ktq;
+  const int ntiles = max(0, min(KT, kt_begin + ktq) - kt_begin);
+  const int ntiles_pad = (ntiles + D - 1) / D * D;
+  const int rot = ntiles_pad > 0 ? (vt * 5 + wave * 3) % ntiles_pad : 0;
+  auto ktile = [&](int t, bool& valid) {     // see lm_head_kernel: loads are never predicated
+    int r = t + rot;
+    if (r >= ntiles_pad) r -= ntiles_pad;
+    valid = t < ntiles_pad && r < ntiles;
+    return valid ? kt_begin + r : 0;
+  };
+  uint16_t* const Ws = reinterpret_cast<uint16_t*>(lds_raw) + wave * (32 + HROWS) * PITCH;
+  uint16_t* const Hs = Ws + 32 * PITCH;
+
+  const char* const Wb = reinterpret_cast<const char*>(a.W);
+  const char* const Hb = reinterpret_cast<const char*>(a.h);
+  const uint32_t kclamp = static_cast<uint32_t>(d - 8) * 2u;
+  uint32_t woff[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+    woff[i] = static_cast<uint32_t>(min(v0 + lrow + 8 * i, a.n - 1)) * static_cast<uint32_t>(d) * 2u;
+  constexpr int HL = HROWS / 8;                  // loads per lane per h tile
+  uint32_t hoff[HL];
+  bool hok[HL];
+#pragma unroll
+  for (int i = 0; i < HL; ++i) {
+    const int rr = lrow + 8 * i;
+    const int blk = rr >> 5, r = rr & 31;
+    const int rb = rb0 + blk / C, c = blk % C;
+    const int b = rb / nLb, s = (rb % nLb) * 32 + r;
+    hok[i] = rb < nRB && s < a.L;
+    hoff[i] = hok[i] ? static_cast<uint32_t>((b * C + c) * a.L + s) * static_cast<uint32_t>(d) * 2u : 0u;
+  }
+  u32x4 wreg[D][4], hreg[DH][HL];
+  bool hkok[DH];
+  auto wload = [&](int slot, int t) {
+    bool valid;
+    const int kt = ktile(t, valid);
+    const uint32_t kb = min(static_cast<uint32_t>(kt * BK + chunk * 8) * 2u, kclamp);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) wreg[slot][i] = *reinterpret_cast<const u32x4*>(Wb + (woff[i] + kb));
+  };
+  auto hload = [&](int slot, int t) {
+    bool valid;
+    const int kt = ktile(t, valid);
+    const int k = kt * BK + chunk * 8;
+    const bool kok = valid && k < d;
+    const uint32_t kb = min(static_cast<uint32_t>(k) * 2u, kclamp);
+#pragma unroll
+    for (int i = 0; i < HL; ++i) hreg[slot][i] = *reinterpret_cast<const u32x4*>(Hb + (hoff[i] + kb));
+    hkok[slot] = kok;
+  };
+  f32x16 acc[NBLK];
+#pragma unroll
+  for (int i = 0; i < NBLK; ++i)
+#pragma unroll
+    for (int j = 0; j < 16; ++j) acc[i][j] = 0.f;
+
+  static_assert(D % DH == 0, "register stages of h must be static in the unrolled body");
+#pragma unroll
+  for (int j = 0; j < D; ++j) wload(j, j);
+#pragma unroll
+  for (int j = 0; j < DH; ++j) hload(j, j);
+  for (int t0 = 0; t0 < ntiles_pad; t0 += D) {
+#pragma unroll
+    for (int j = 0; j < D; ++j) {
+      compiler_fence();
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+        *reinterpret_cast<u32x4*>(&Ws[(lrow + 8 * i) * PITCH + chunk * 8]) = wreg[j][i];
+#pragma unroll
+      for (int i = 0; i < HL; ++i) {          // zeroing here: at the load it would wait for it
+        const u32x4 t4 = hreg[j % DH][i];
+        const bool keep = hok[i] && hkok[j % DH];
+        *reinterpret_cast<u32x4*>(&Hs[(lrow + 8 * i) * PITCH + chunk * 8]) =
+            (keep ? t4 : u32x4{0u, 0u, 0u, 0u});
+      }
+      wload(j, t0 + j + D);
+      hload(j % DH, t0 + j + DH);
+      compiler_fence();
+#pragma unroll
+      for (int kk = 0; kk < BK / 16; ++kk) {
+        const u32x4 braw = *reinterpret_cast<const u32x4*>(&Ws[ln * PITCH + kk * 16 + lg * 8]);
+        const bf16x8 bfrag = __builtin_bit_cast(bf16x8, braw);
+#pragma unroll
+        for (int i = 0; i < NBLK; ++i) {
+          const u32x4 araw = *reinterpret_cast<const u32x4*>(&Hs[(i * 32 + ln) * PITCH + kk * 16 + lg * 8]);
+          acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, araw), bfrag,
+                                                           acc[i], 0, 0, 0);
+        }
+      }
+      compiler_fence();
+    }
+  }
+  // sum of the partial accumulators in wavefront order 0, 1, 2, ... through LDS
+  __syncthreads();
+  float* red = reinterpret_cast<float*>(lds_raw);
+#pragma unroll
+  for (int i = 0; i < NBLK; ++i)
+#pragma unroll
+    for (int j = 0; j < 16; ++j) red[((wave * NBLK + i) * 16 + j) * 64 + lane] = acc[i][j];
+  __syncthreads();
+#pragma unroll
+  for (int i = 0; i < NBLK; ++i)
+#pragma unroll
+    for (int j = 0; j < 16; ++j) {
+      float sum = red[((0 * NBLK + i) * 16 + j) * 64 + lane];
+#pragma unroll
+      for (int w = 1; w < NWAVE; ++w) sum += red[((w * NBLK + i) * 16 + j) * 64 + lane];
+      acc[i][j] = sum;
+    }
+  // every wavefront holds the full sums; wavefront w stores the elements j % NWAVE == w
+  epilogue<RBW, C>(a, acc, nLb, nRB, rb0, v0, ln, lg, wave, 16, NWAVE);
+}
+
+template <int RBW, int C, int NWV>
+hipError_t launch_wide(const LmHeadArgs& a, hipStream_t s) {
+  using K = Cfg<RBW, C, NWV>;
   const int nLb = (a.L + 31) / 32;
   const int nRB = a.B * nLb;
   const int VT = (a.n + K::BN - 1) / K::BN;
   const int MT = (nRB + RBW - 1) / RBW;
-  const int VT8 = (VT + 7) / 8 * 8;
-  const int grid = VT8 * MT;
-  hipLaunchKernelGGL((lm_head_kernel<RBW, C, KS, NWV>), dim3(grid), dim3(K::THREADS), 0, s, a, nLb, nRB,
+  const int grid = (VT + 7) / 8 * 8 * MT;
+  hipLaunchKernelGGL((lm_head_kernel<RBW, C, NWV>), dim3(grid), dim3(K::THREADS), 0, s, a, nLb, nRB,
                      VT, MT);
+  return hipGetLastError();
+}
+
+template <int RBW, int C, int KS>
+hipError_t launch_split(const LmHeadArgs& a, hipStream_t s) {
+  using K = SplitCfg<RBW, C, KS>;
+  const int nLb = (a.L + 31) / 32;
+  const int nRB = a.B * nLb;
+  const int VT = (a.n + 31) / 32;
+  const int MT = (nRB + RBW - 1) / RBW;
+  const int grid = (VT + 7) / 8 * 8 * MT;
+  hipLaunchKernelGGL((lm_head_splitk_kernel<RBW, C, KS>), dim3(grid), dim3(K::THREADS), 0, s, a, nLb,
+                     nRB, VT, MT);
   return hipGetLastError();
 }
 
@@ -339,15 +448,14 @@ template <int C>
 hipError_t launch_c(const LmHeadArgs& a, hipStream_t s) {
   const int nRB = a.B * ((a.L + 31) / 32);
   const int KT = (a.d + BK - 1) / BK;
-  // Narrow vocabularies: with 128-column workgroups fewer than ~1.5 per CU would
-  // exist; split k inside the workgroup instead and give every workgroup 32 columns.
+  // Narrow vocabularies: with 128-column workgroups fewer than ~1.5 per CU would exist;
+  // split k inside the workgroup instead and give every workgroup 32 columns.
   const bool narrow = (a.n + 127) / 128 < 384 && KT >= 16;
-  if (nRB >= 4) return launch_t<4, C, 1>(a, s);
-  if (nRB >= 2) return narrow ? launch_t<2, C, 4>(a, s) : launch_t<2, C, 1>(a, s);
-  if (narrow && KT >= 48) return launch_t<1, C, 8>(a, s);
-  if (narrow) return launch_t<1, C, 4>(a, s);
+  if (nRB >= 4) return launch_wide<4, C, 4>(a, s);
+  if (nRB >= 2) return narrow ? launch_split<2, C, 4>(a, s) : launch_wide<2, C, 4>(a, s);
+  if (narrow) return KT >= 48 ? launch_split<1, C, 8>(a, s) : launch_split<1, C, 4>(a, s);
   // wide vocabulary: 8 wavefronts share each h tile (halves the h traffic out of L2)
-  return (a.n + 255) / 256 >= 200 ? launch_t<1, C, 1, 8>(a, s) : launch_t<1, C, 1, 4>(a, s);
+  return (a.n + 255) / 256 >= 200 ? launch_wide<1, C, 8>(a, s) : launch_wide<1, C, 4>(a, s);
 }
 
 }  // namespace

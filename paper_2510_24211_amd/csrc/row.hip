@@ -908,30 +908,42 @@ __global__ __launch_bounds__(THREADS) void row_kernel(const RowArgs a, const int
       k_out = 0;
     }
   }
-  if (tid == 0) {
-    a.y[R.widx] = y_out;
-    a.k[R.widx] = static_cast<uint8_t>(k_out);
-    if (a.px) a.px[R.widx] = out.px;
-    if (a.qx) a.qx[R.widx] = out.qx;
+  if (a.mode != kRowRing) {
+    if (tid == 0) {
+      a.y[R.widx] = y_out;
+      a.k[R.widx] = static_cast<uint8_t>(k_out);
+      if (a.px) a.px[R.widx] = out.px;
+      if (a.qx) a.qx[R.widx] = out.qx;
+    }
+    return;
   }
-  if (a.mode != kRowRing) return;
 
   // ---- last workgroup of the sequence: first rejection, emit, slide -----------
+  // Hand-off between workgroups WITHOUT an agent-scope fence (on this chip such a fence
+  // writes back the whole L2 and costs tens of microseconds per launch): the few bytes
+  // that travel (y, k) are stored with agent-scope atomic stores, which go straight to
+  // the device-coherent level; the wavefront waits for their completion (workgroup-scope
+  // release = s_waitcnt) before it bumps the ticket with an agent-scope atomic; the last
+  // arriver reads them back with agent-scope atomic loads.
   const int b = R.b, p0 = R.p0, live = R.live;
   if (tid == 0) {
-    __threadfence();
-    sm.last = atomicAdd(&a.ticket[b], 1) == live - 1;
+    __hip_atomic_store(&a.y[R.widx], y_out, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    __hip_atomic_store(&a.k[R.widx], static_cast<uint8_t>(k_out), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (a.px) a.px[R.widx] = out.px;
+    if (a.qx) a.qx[R.widx] = out.qx;
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+    sm.last = __hip_atomic_fetch_add(&a.ticket[b], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == live - 1;
     sm.first_rej = live;
   }
   __syncthreads();
   if (!sm.last) return;
-  __threadfence();
-  const volatile int32_t* vy = a.y + static_cast<size_t>(b) * a.L;
-  const volatile uint8_t* vk = a.k + static_cast<size_t>(b) * a.L;
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
   int yy = -1;
   if (tid < live) {
-    yy = vy[tid];
-    if (vk[tid] == 0) atomicMin(&sm.first_rej, tid);
+    yy = __hip_atomic_load(&a.y[static_cast<size_t>(b) * a.L + tid], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    const uint8_t kk = __hip_atomic_load(&a.k[static_cast<size_t>(b) * a.L + tid], __ATOMIC_RELAXED,
+                                         __HIP_MEMORY_SCOPE_AGENT);
+    if (kk == 0) atomicMin(&sm.first_rej, tid);
   }
   __syncthreads();
   const int acc = min(sm.first_rej + 1, live);
