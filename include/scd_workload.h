@@ -23,6 +23,13 @@ int scdw_gather_hidden(void* hip_stream, const uint16_t* d_table, int32_t B, int
                        int32_t N, int32_t d, int32_t age_cap, const int32_t* d_pos,
                        const int32_t* d_age, uint16_t* d_h);
 
+/* Plain device copy d_dst[0 .. bytes) = d_src[0 .. bytes) by one kernel (copy_kernel) that
+ * reads and writes every byte exactly once with 16-byte accesses.  It exists so that a
+ * profiler's HBM byte counters can be scaled by what they report for a transfer of known
+ * size.  bytes must be a multiple of 16, both pointers 16-byte aligned and the ranges
+ * disjoint.  Asynchronous on hip_stream.  Returns 0, -1 (bad argument) or -3. */
+int scdw_copy(void* hip_stream, const void* d_src, void* d_dst, size_t bytes);
+
 #ifdef __cplusplus
 }
 #endif

@@ -77,10 +77,11 @@ def load():
     lib.scd_strerror.restype = ctypes.c_char_p
     lib.scd_strerror.argtypes = [ctypes.c_int]
     lib.scdw_gather_hidden.argtypes = [vp, vp, i32, i32, i32, i32, i32, i32, vp, vp, vp]
+    lib.scdw_copy.argtypes = [vp, vp, vp, sz]
     for name in ("scd_create", "scd_destroy", "scd_reset", "scd_state_field", "scd_lm_head",
                  "scd_select", "scd_couple_draft", "scd_verify", "scd_step", "scd_step_logits",
                  "scd_set_lm_head_events",
-                 "scd_status", "scdw_gather_hidden"):
+                 "scd_status", "scdw_gather_hidden", "scdw_copy"):
         getattr(lib, name).restype = ctypes.c_int
     _lib = lib
     return lib
@@ -242,6 +243,19 @@ class Scd:
             ctypes.c_void_p(self.state_field(state, F_AGE).data_ptr()),
             _ptr(h, _BF16, c.B * self.C * c.L * c.d, "h"))
         self._check(rc, "scdw_gather_hidden")
+
+
+def device_copy(src, dst, stream=None):
+    """dst <- src by the library's plain copy kernel (profiler counter calibration)."""
+    assert src.is_cuda and dst.is_cuda and src.is_contiguous() and dst.is_contiguous()
+    nbytes = src.numel() * src.element_size()
+    assert nbytes == dst.numel() * dst.element_size()
+    st = stream if stream is not None else torch.cuda.current_stream(src.device)
+    rc = load().scdw_copy(ctypes.c_void_p(st.cuda_stream), ctypes.c_void_p(src.data_ptr()),
+                          ctypes.c_void_p(dst.data_ptr()), nbytes)
+    if rc != 0:
+        raise RuntimeError(f"scdw_copy failed with {rc}")
+    return nbytes
 
 
 def config_from_workload(w):

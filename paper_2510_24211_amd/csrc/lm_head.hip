@@ -44,6 +44,9 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 constexpr int BK = 64;          // k elements per W tile (128 bytes per row)
 constexpr int PITCH = BK + 8;   // LDS row pitch in bf16 elements (144 bytes)
 
+struct TrueT { static constexpr bool value = true; };
+struct FalseT { static constexpr bool value = false; };
+
 __device__ __forceinline__ void compiler_fence() { asm volatile("" ::: "memory"); }
 
 template <int RBW, int C, int NWV>
@@ -63,44 +66,57 @@ struct Cfg {
   static constexpr int LDS_BYTES = (W_LDS + H_LDS) * 2;
 };
 
-// Epilogue for the accumulator elements j = j0, j0 + jstep, ... < j1.  Element j of lane
-// (ln, lg) is row (j/4)*8 + lg*4 + j%4, column ln of the 32x32 tile.
+// Where the 32 window positions of row block rb (sequence b, positions sbase..sbase+31 of
+// its window) are stored: ring slot (pos[b] + s) % L of half iter[b] & 1 when the decode
+// state is given, row s otherwise.
+struct RowBlockDst {
+  float* zb;
+  int b, sbase, p0, live;
+};
+__device__ __forceinline__ RowBlockDst row_block_dst(const LmHeadArgs& a, int rb, int nLb) {
+  RowBlockDst r;
+  r.b = rb / nLb;
+  r.sbase = (rb % nLb) * 32;
+  r.p0 = 0;
+  r.live = a.L;
+  r.zb = a.z;
+  if (a.pos) {
+    r.p0 = a.pos[r.b];
+    r.live = min(a.L, a.N - r.p0);
+  }
+  if (a.iter) r.zb += static_cast<size_t>(a.iter[r.b] & 1) * a.parity_stride;
+  return r;
+}
+
+// Guidance mix and temperature of one logit (cond sum c, uncond sum u), stored for window
+// position s and allowed id v.
+template <int C>
+__device__ __forceinline__ void store_logit(const LmHeadArgs& a, const RowBlockDst& r, int s, int v,
+                                            float c, float u) {
+  if (s >= r.live) return;
+  float z = c;
+  if (C == 2) z = __fsub_rn(__fmul_rn(a.one_plus_lam, c), __fmul_rn(a.lam, u));
+  z = __fdiv_rn(z, a.tau);
+  const int slot = a.pos ? (r.p0 + s) % a.L : s;
+  r.zb[(static_cast<size_t>(r.b) * a.L + slot) * a.n + v] = z;
+}
+
+// Epilogue of a wavefront that holds whole sums.  Element j of lane (ln, lg) is row
+// (j/4)*8 + lg*4 + j%4, column ln of the 32x32 tile.
 template <int RBW, int C>
 __device__ __forceinline__ void epilogue(const LmHeadArgs& a, const f32x16 (&acc)[RBW * C], int nLb,
-                                         int nRB, int rb0, int v0, int ln, int lg, int j0, int j1,
-                                         int jstep) {
+                                         int nRB, int rb0, int v0, int ln, int lg) {
   const int v = v0 + ln;
   if (v >= a.n) return;
 #pragma unroll
   for (int rbw = 0; rbw < RBW; ++rbw) {
     const int rb = rb0 + rbw;
     if (rb >= nRB) break;
-    const int b = rb / nLb;
-    const int sbase = (rb % nLb) * 32;
-    int p0 = 0, live = a.L;
-    float* zb = a.z;
-    if (a.pos) {
-      p0 = a.pos[b];
-      live = min(a.L, a.N - p0);
-    }
-    if (a.iter) zb += static_cast<size_t>(a.iter[b] & 1) * a.parity_stride;
+    const RowBlockDst r = row_block_dst(a, rb, nLb);
 #pragma unroll
-    for (int j = 0; j < 16; ++j) {
-      if (j < j0 || j >= j1 || (j - j0) % jstep != 0) continue;
-      const int s = sbase + (j >> 2) * 8 + lg * 4 + (j & 3);
-      if (s >= live) continue;
-      float z;
-      if (C == 2) {
-        const float t0 = __fmul_rn(a.one_plus_lam, acc[rbw * C][j]);
-        const float t1 = __fmul_rn(a.lam, acc[rbw * C + C - 1][j]);
-        z = __fsub_rn(t0, t1);
-      } else {
-        z = acc[rbw * C][j];
-      }
-      z = __fdiv_rn(z, a.tau);
-      const int slot = a.pos ? (p0 + s) % a.L : s;
-      zb[(static_cast<size_t>(b) * a.L + slot) * a.n + v] = z;
-    }
+    for (int j = 0; j < 16; ++j)
+      store_logit<C>(a, r, r.sbase + (j >> 2) * 8 + lg * 4 + (j & 3), v, acc[rbw * C][j],
+                     acc[rbw * C + C - 1][j]);
   }
 }
 
@@ -225,32 +241,51 @@ __global__ __launch_bounds__((Cfg<RBW, C, NWV>::THREADS)) void lm_head_kernel(
 #pragma unroll
     for (int j = 0; j < 16; ++j) acc[i][j] = 0.f;
 
-  // MFMAs of one W tile against h tile `Hs_tile` at column offset koff
+  // MFMAs of one W tile against h tile `Hs_tile` at column offset koff.  The operands of
+  // k-step kk + 1 are read from LDS before the MFMAs of k-step kk are issued, so that the
+  // matrix pipe does not wait for an LDS round trip per instruction.
   auto compute = [&](const uint16_t* Hs_tile, int koff) {
+    constexpr int KK = BK / 16;
+    u32x4 bq[2], aq[2][NBLK];
+    auto fetch = [&](int buf, int kk) {
+      bq[buf] = *reinterpret_cast<const u32x4*>(&Ws[ln * PITCH + kk * 16 + lg * 8]);
 #pragma unroll
-    for (int kk = 0; kk < BK / 16; ++kk) {
-      const u32x4 braw = *reinterpret_cast<const u32x4*>(&Ws[ln * PITCH + kk * 16 + lg * 8]);
-      const bf16x8 bfrag = __builtin_bit_cast(bf16x8, braw);
-#pragma unroll
-      for (int i = 0; i < NBLK; ++i) {
-        const u32x4 araw = *reinterpret_cast<const u32x4*>(
+      for (int i = 0; i < NBLK; ++i)
+        aq[buf][i] = *reinterpret_cast<const u32x4*>(
             &Hs_tile[(i * 32 + ln) * K::PITCH_H + koff + kk * 16 + lg * 8]);
-        acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, araw), bfrag,
-                                                         acc[i], 0, 0, 0);
+    };
+    fetch(0, 0);
+#pragma unroll
+    for (int kk = 0; kk < KK; ++kk) {
+      if (kk + 1 < KK) fetch((kk + 1) & 1, kk + 1);
+      const bf16x8 bfrag = __builtin_bit_cast(bf16x8, bq[kk & 1]);
+#pragma unroll
+      for (int i = 0; i < NBLK; ++i)
+        acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, aq[kk & 1][i]),
+                                                         bfrag, acc[i], 0, 0, 0);
+      if (kk + 1 < KK) {                       // keep that order: reads of kk + 1, MFMAs of kk
+        __builtin_amdgcn_sched_group_barrier(0x100, NBLK + 1, 0);
+        __builtin_amdgcn_sched_group_barrier(0x008, NBLK, 0);
       }
     }
   };
 
-  // h tile st is loaded into register stage st % 2 two h tiles ahead, moved to LDS buffer
-  // st % 2 at the end of h tile st - 1, and consumed during h tile st.
+  // h tile st travels: registers (stage st % 2, loaded at the end of h tile st - 3), LDS
+  // buffer st % 2 (moved at the end of h tile st - 1), consumed during h tile st.  One
+  // barrier per h tile: it publishes the moved tile and ends the reads of the buffer that
+  // the next move overwrites.
   static_assert(D % (2 * HT) == 0, "register stages of h must be static in the unrolled body");
 #pragma unroll
   for (int j = 0; j < D; ++j) wload(j, j);
   hload(0, 0);
-  hload(1, 1);
   hstore(0, 0);
+  hload(1, 1);
+  hload(0, 2);
   __syncthreads();
-  for (int t0 = 0; t0 < ntiles_pad; t0 += D) {
+  // One pass over D tiles.  The last pass (PF false) issues no load that would fall past
+  // the end: such a load would fetch real bytes a second time.
+  auto body = [&](int t0, auto pf) {
+    constexpr bool PF = decltype(pf)::value;
 #pragma unroll
     for (int j = 0; j < D; ++j) {
       const int t = t0 + j;
@@ -258,19 +293,21 @@ __global__ __launch_bounds__((Cfg<RBW, C, NWV>::THREADS)) void lm_head_kernel(
       const int stage = (j / HT) & 1;            // == st & 1 because t0 / HT is even
       compiler_fence();
       wstore(j);
-      wload(j, t + D);
+      if (PF) wload(j, t + D);
       compiler_fence();
       compute(Hs_all + stage * HROWS * K::PITCH_H, (j % HT) * BK);
       compiler_fence();
-      if (j % HT == HT - 1) {
+      if (j % HT == HT - 1 && (PF || j / HT + 1 < D / HT)) {
         hstore(stage ^ 1, stage ^ 1);            // h tile st + 1 -> the other LDS buffer
-        hload(stage, st + 2);                    // h tile st + 2 -> the register stage just freed
+        if (PF || j / HT + 3 < D / HT) hload(stage ^ 1, st + 3);
         __syncthreads();
       }
     }
-  }
+  };
+  for (int t0 = 0; t0 < ntiles_pad - D; t0 += D) body(t0, TrueT{});
+  body(ntiles_pad - D, FalseT{});
 
-  epilogue<RBW, C>(a, acc, nLb, nRB, rb0, v0, ln, lg, 0, 16, 1);
+  epilogue<RBW, C>(a, acc, nLb, nRB, rb0, v0, ln, lg);
 }
 
 // ---- narrow vocabularies: k split over the wavefronts of a workgroup ---------------------
@@ -366,7 +403,8 @@ __global__ __launch_bounds__((SplitCfg<RBW, C, KS>::THREADS)) void lm_head_split
   for (int j = 0; j < D; ++j) wload(j, j);
 #pragma unroll
   for (int j = 0; j < DH; ++j) hload(j, j);
-  for (int t0 = 0; t0 < ntiles_pad; t0 += D) {
+  auto body = [&](int t0, auto pf) {           // PF false: the last pass, no loads past the end
+    constexpr bool PF = decltype(pf)::value;
 #pragma unroll
     for (int j = 0; j < D; ++j) {
       compiler_fence();
@@ -380,8 +418,8 @@ __global__ __launch_bounds__((SplitCfg<RBW, C, KS>::THREADS)) void lm_head_split
         *reinterpret_cast<u32x4*>(&Hs[(lrow + 8 * i) * PITCH + chunk * 8]) =
             (keep ? t4 : u32x4{0u, 0u, 0u, 0u});
       }
-      wload(j, t0 + j + D);
-      hload(j % DH, t0 + j + DH);
+      if (PF) wload(j, t0 + j + D);
+      if (PF || j + DH < D) hload(j % DH, t0 + j + DH);
       compiler_fence();
 #pragma unroll
       for (int kk = 0; kk < BK / 16; ++kk) {
@@ -396,8 +434,12 @@ __global__ __launch_bounds__((SplitCfg<RBW, C, KS>::THREADS)) void lm_head_split
       }
       compiler_fence();
     }
+  };
+  if (ntiles_pad > 0) {
+    for (int t0 = 0; t0 < ntiles_pad - D; t0 += D) body(t0, TrueT{});
+    body(ntiles_pad - D, FalseT{});
   }
-  // sum of the partial accumulators in wavefront order 0, 1, 2, ... through LDS
+  // the partial accumulators meet in LDS
   __syncthreads();
   float* red = reinterpret_cast<float*>(lds_raw);
 #pragma unroll
@@ -405,17 +447,28 @@ __global__ __launch_bounds__((SplitCfg<RBW, C, KS>::THREADS)) void lm_head_split
 #pragma unroll
     for (int j = 0; j < 16; ++j) red[((wave * NBLK + i) * 16 + j) * 64 + lane] = acc[i][j];
   __syncthreads();
+  // wavefront w adds up (partial sums in wavefront order 0, 1, 2, ...) and stores the
+  // accumulator elements j = w, w + NWAVE, ... of every tile
+  const int v = v0 + ln;
+  if (v >= a.n) return;
 #pragma unroll
-  for (int i = 0; i < NBLK; ++i)
+  for (int rbw = 0; rbw < RBW; ++rbw) {
+    const int rb = rb0 + rbw;
+    if (rb >= nRB) break;
+    const RowBlockDst r = row_block_dst(a, rb, nLb);
 #pragma unroll
-    for (int j = 0; j < 16; ++j) {
-      float sum = red[((0 * NBLK + i) * 16 + j) * 64 + lane];
+    for (int jj = 0; jj < 16 / NWAVE; ++jj) {
+      const int j = wave + jj * NWAVE;
+      float c = red[((0 * NBLK + rbw * C) * 16 + j) * 64 + lane];
+      float u = red[((0 * NBLK + rbw * C + C - 1) * 16 + j) * 64 + lane];
 #pragma unroll
-      for (int w = 1; w < NWAVE; ++w) sum += red[((w * NBLK + i) * 16 + j) * 64 + lane];
-      acc[i][j] = sum;
+      for (int w = 1; w < NWAVE; ++w) {
+        c += red[((w * NBLK + rbw * C) * 16 + j) * 64 + lane];
+        u += red[((w * NBLK + rbw * C + C - 1) * 16 + j) * 64 + lane];
+      }
+      store_logit<C>(a, r, r.sbase + (j >> 2) * 8 + lg * 4 + (j & 3), v, c, u);
     }
-  // every wavefront holds the full sums; wavefront w stores the elements j % NWAVE == w
-  epilogue<RBW, C>(a, acc, nLb, nRB, rb0, v0, ln, lg, wave, 16, NWAVE);
+  }
 }
 
 template <int RBW, int C, int NWV>

@@ -154,15 +154,7 @@ __global__ __launch_bounds__(THREADS) void mrs_kernel(const MrsArgs a) {
     }
   }
   // lexicographic (score, id) minimum over the workgroup
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) {
-    const float os = __shfl_xor(best, o, kWave);
-    const int oi = __shfl_xor(best_id, o, kWave);
-    if (os < best || (os == best && oi < best_id)) {
-      best = os;
-      best_id = oi;
-    }
-  }
+  wave_min_score_id(best, best_id);
   if ((tid & 63) == 0) {
     s_score[tid >> 6] = best;
     s_id[tid >> 6] = best_id;

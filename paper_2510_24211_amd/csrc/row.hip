@@ -49,11 +49,11 @@ constexpr int NW = THREADS / kWave;
 constexpr int NBINS = 4096;
 constexpr int kListCap = 6144;               // candidate ids per row (LDS list / slice output)
 constexpr int PER_LIST = kListCap / THREADS; // candidates per thread
-constexpr int kDirectMaxN = 8192;            // whole row in registers up to this many ids
-constexpr int PER_DIRECT = kDirectMaxN / THREADS;
+constexpr int kDirectMaxN = 16384;           // whole row in registers up to this many ids
+constexpr int PER_DIRECT = kDirectMaxN / THREADS;   // (rows of half that size take half of them)
 constexpr int kSliceMax = 8192;              // logits per slice workgroup
 constexpr int PER_SLICE = kSliceMax / THREADS;
-static_assert(THREADS >= 256 && kListCap % THREADS == 0 && PER_DIRECT % 4 == 0 && PER_SLICE % 4 == 0,
+static_assert(THREADS >= 256 && kListCap % THREADS == 0 && PER_DIRECT % 8 == 0 && PER_SLICE % 4 == 0,
               "row kernels: unsupported workgroup size");
 constexpr int kKeptCap = 4096;               // kept ids compacted in LDS
 
@@ -85,12 +85,7 @@ __device__ __forceinline__ uint32_t find_bin(const uint32_t* hist, uint32_t& nee
     c[j] = hist[NBINS - 1 - (tid * PER + j)];
     local += c[j];
   }
-  uint32_t incl = local;
-#pragma unroll
-  for (int o = 1; o < 64; o <<= 1) {
-    const uint32_t t = static_cast<uint32_t>(__shfl_up(static_cast<int>(incl), o, kWave));
-    if (lane >= o) incl += t;
-  }
+  uint32_t incl = static_cast<uint32_t>(wave_inclusive_sum_i32(static_cast<int>(local), lane));
   if (lane == 63) sm.wtot[wave] = incl;
   __syncthreads();
   uint32_t base = 0;
@@ -128,12 +123,7 @@ __device__ __forceinline__ float prob(float z, float thr, float lse) {
 // Exclusive offset of this thread's `cnt` in a fixed thread order, and the total.
 __device__ __forceinline__ int block_offsets(int cnt, int& total, Small& sm) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  int incl = cnt;
-#pragma unroll
-  for (int o = 1; o < 64; o <<= 1) {
-    const int t = __shfl_up(incl, o, kWave);
-    if (lane >= o) incl += t;
-  }
+  const int incl = wave_inclusive_sum_i32(cnt, lane);
   if (lane == 63) sm.ired[wave] = incl;
   __syncthreads();
   int base = 0;
@@ -396,12 +386,15 @@ struct RowOut {      // what a path hands to the common tail
 // Everything after the candidates sit in registers: threshold (if top-k filters),
 // normaliser, accept test, residual race.  Returns false if the threshold could not
 // be certified against `cut_max` (the caller then takes the complete path).
+// zq[e] is the previous iteration's logit of id vid[e] (read by the caller together with
+// zv, long before a rejection may need it; unused for a fresh position).  The LDS arrays
+// cid / cz / cq hold ccap entries each.
 template <int PER>
 __device__ __forceinline__ bool finish_regs(const RowArgs& a, const RowRef& R, const int (&vid)[PER],
-                                            const float (&zv)[PER], const bool (&ok)[PER],
-                                            bool filter, uint32_t cut_max, float zcx, float zpx,
-                                            uint32_t* hist, uint32_t* cid, float* cz, int ccap,
-                                            Small& sm, RowOut& out) {
+                                            const float (&zv)[PER], const float (&zq)[PER],
+                                            const bool (&ok)[PER], bool filter, uint32_t cut_max,
+                                            float zcx, float zpx, uint32_t* hist, uint32_t* cid,
+                                            float* cz, float* cq, int ccap, Small& sm, RowOut& out) {
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int n = a.n;
   uint32_t kv[PER], kmax = 0, kmin = 0xFFFFFFFFu;
@@ -441,6 +434,7 @@ __device__ __forceinline__ bool finish_regs(const RowArgs& a, const RowRef& R, c
       if (kept[e]) {
         cid[off] = static_cast<uint32_t>(vid[e]);
         cz[off] = zv[e];
+        cq[off] = zq[e];
         ++off;
       }
     }
@@ -504,9 +498,8 @@ __device__ __forceinline__ bool finish_regs(const RowArgs& a, const RowRef& R, c
       const int i = tid + q * THREADS;
       rid[q] = i < Cn ? static_cast<int>(cid[i]) : -1;
       rz[q] = i < Cn ? cz[i] : 0.f;
+      rq[q] = i < Cn ? cq[i] : 0.f;
     }
-#pragma unroll
-    for (int q = 0; q < KPT; ++q) rq[q] = (!R.fresh && rid[q] >= 0) ? R.zp[rid[q]] : 0.f;
     int npos = 0;
 #pragma unroll
     for (int q = 0; q < KPT; ++q) {
@@ -532,9 +525,6 @@ __device__ __forceinline__ bool finish_regs(const RowArgs& a, const RowRef& R, c
     __syncthreads();
     for (int i = tid; i < ntot; i += THREADS) race_one(static_cast<int>(cid[i]), cz[i]);
   } else {
-    float zq[PER];
-#pragma unroll
-    for (int e = 0; e < PER; ++e) zq[e] = (!R.fresh && kept[e]) ? R.zp[vid[e]] : 0.f;
 #pragma unroll
     for (int e = 0; e < PER; ++e) {
       if (kept[e]) {
@@ -683,11 +673,15 @@ __device__ __forceinline__ void full_path(const RowArgs& a, const RowRef& R, uns
     }
 #pragma unroll
     for (int e = 0; e < PER_LIST; ++e) zv[e] = ok[e] ? zc[vid[e]] : 0.f;
+    float zq[PER_LIST];
+    const bool want_q = a.mode != kRowSelectOnly && !R.fresh;
+#pragma unroll
+    for (int e = 0; e < PER_LIST; ++e) zq[e] = (want_q && ok[e]) ? R.zp[vid[e]] : 0.f;
     // the prefixes in LDS are spent: their space takes the compaction arrays
-    const int ccap = min(kKeptCap, static_cast<int>(static_cast<size_t>(n8) * 2 / 8));
-    finish_regs<PER_LIST>(a, R, vid, zv, ok, true, 0u, zcx, zpx, hist,
-                          reinterpret_cast<uint32_t*>(smem), reinterpret_cast<float*>(smem) + ccap, ccap, sm,
-                          out);
+    const int ccap = min(kKeptCap, static_cast<int>(static_cast<size_t>(n8) * 2 / 12));
+    finish_regs<PER_LIST>(a, R, vid, zv, zq, ok, true, 0u, zcx, zpx, hist,
+                          reinterpret_cast<uint32_t*>(smem), reinterpret_cast<float*>(smem) + ccap,
+                          reinterpret_cast<float*>(smem) + 2 * ccap, ccap, sm, out);
     return;
   }
 
@@ -787,6 +781,45 @@ __device__ __forceinline__ void full_path(const RowArgs& a, const RowRef& R, uns
   }
 }
 
+// The whole row in registers, PER logits per thread (n <= PER * THREADS).
+template <int PER>
+__device__ __forceinline__ void direct_path(const RowArgs& a, const RowRef& R, unsigned char* smem,
+                                            bool filter, float zcx, float zpx, Small& sm, RowOut& out) {
+  const int tid = threadIdx.x, n = a.n;
+  uint32_t* hist = reinterpret_cast<uint32_t*>(smem);
+  const bool vec_ok = (n & 3) == 0;
+  const bool want_q = a.mode != kRowSelectOnly && !R.fresh;   // previous logits, for a rejection
+  int vid[PER];
+  float zv[PER], zq[PER];
+  bool ok[PER];
+#pragma unroll
+  for (int u = 0; u < PER / 4; ++u) {
+    const int v0 = (tid + u * THREADS) << 2;
+    if (vec_ok && v0 + 3 < n) {
+      const float4 t = *reinterpret_cast<const float4*>(R.zc + v0);
+      zv[u * 4 + 0] = t.x; zv[u * 4 + 1] = t.y; zv[u * 4 + 2] = t.z; zv[u * 4 + 3] = t.w;
+      float4 q = make_float4(0.f, 0.f, 0.f, 0.f);
+      if (want_q) q = *reinterpret_cast<const float4*>(R.zp + v0);
+      zq[u * 4 + 0] = q.x; zq[u * 4 + 1] = q.y; zq[u * 4 + 2] = q.z; zq[u * 4 + 3] = q.w;
+    } else {
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        zv[u * 4 + e] = (v0 + e < n) ? R.zc[v0 + e] : 0.f;
+        zq[u * 4 + e] = (want_q && v0 + e < n) ? R.zp[v0 + e] : 0.f;
+      }
+    }
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      vid[u * 4 + e] = v0 + e;
+      ok[u * 4 + e] = v0 + e < n;
+    }
+  }
+  uint32_t* cid = hist + NBINS;
+  finish_regs<PER>(a, R, vid, zv, zq, ok, filter, 0u, zcx, zpx, hist, cid,
+                   reinterpret_cast<float*>(cid + kKeptCap),
+                   reinterpret_cast<float*>(cid + 2 * kKeptCap), kKeptCap, sm, out);
+}
+
 __global__ __launch_bounds__(THREADS) void row_kernel(const RowArgs a, const int P, const int capE) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   __shared__ Small sm;
@@ -815,30 +848,8 @@ __global__ __launch_bounds__(THREADS) void row_kernel(const RowArgs a, const int
   bool done = false;
   if (n <= kDirectMaxN) {
     // ---- the whole row in registers ------------------------------------------------
-    uint32_t* hist = reinterpret_cast<uint32_t*>(smem);
-    const bool vec_ok = (n & 3) == 0;
-    int vid[PER_DIRECT];
-    float zv[PER_DIRECT];
-    bool ok[PER_DIRECT];
-#pragma unroll
-    for (int u = 0; u < PER_DIRECT / 4; ++u) {
-      const int v0 = (tid + u * THREADS) << 2;
-      if (vec_ok && v0 + 3 < n) {
-        const float4 t = *reinterpret_cast<const float4*>(R.zc + v0);
-        zv[u * 4 + 0] = t.x; zv[u * 4 + 1] = t.y; zv[u * 4 + 2] = t.z; zv[u * 4 + 3] = t.w;
-      } else {
-#pragma unroll
-        for (int e = 0; e < 4; ++e) zv[u * 4 + e] = (v0 + e < n) ? R.zc[v0 + e] : 0.f;
-      }
-#pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        vid[u * 4 + e] = v0 + e;
-        ok[u * 4 + e] = v0 + e < n;
-      }
-    }
-    uint32_t* cid = hist + NBINS;
-    finish_regs<PER_DIRECT>(a, R, vid, zv, ok, filter, 0u, zcx, zpx, hist, cid,
-                            reinterpret_cast<float*>(cid + kKeptCap), kKeptCap, sm, out);
+    if (n <= kDirectMaxN / 2) direct_path<PER_DIRECT / 2>(a, R, smem, filter, zcx, zpx, sm, out);
+    else direct_path<PER_DIRECT>(a, R, smem, filter, zcx, zpx, sm, out);
     done = true;
   } else if (filter && a.cand && P > 0) {
     // ---- candidates emitted by the slice kernel ----------------------------------
@@ -867,10 +878,15 @@ __global__ __launch_bounds__(THREADS) void row_kernel(const RowArgs a, const int
         vid[e] = static_cast<int>(t.x);
         zv[e] = __uint_as_float(t.y);
       }
-      const int ccap = min(kKeptCap, static_cast<int>(static_cast<size_t>((n + 7) & ~7) * 2 / 8));
-      done = finish_regs<PER_LIST>(a, R, vid, zv, ok, true, cut_max, zcx, zpx, hist,
+      float zq[PER_LIST];
+      const bool want_q = a.mode != kRowSelectOnly && !R.fresh;
+#pragma unroll
+      for (int e = 0; e < PER_LIST; ++e)
+        zq[e] = (want_q && ok[e]) ? R.zp[vid[e]] : 0.f;
+      const int ccap = min(kKeptCap, static_cast<int>(static_cast<size_t>((n + 7) & ~7) * 2 / 12));
+      done = finish_regs<PER_LIST>(a, R, vid, zv, zq, ok, true, cut_max, zcx, zpx, hist,
                                    reinterpret_cast<uint32_t*>(smem), reinterpret_cast<float*>(smem) + ccap,
-                                   ccap, sm, out);
+                                   reinterpret_cast<float*>(smem) + 2 * ccap, ccap, sm, out);
     }
   }
   if (!done) full_path(a, R, smem, zcx, zpx, sm, out);
@@ -882,15 +898,7 @@ __global__ __launch_bounds__(THREADS) void row_kernel(const RowArgs a, const int
   if (!out.accept) {
     float best = out.best;
     int best_id = out.best_id;
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) {
-      const float os = __shfl_xor(best, o, kWave);
-      const int oi = __shfl_xor(best_id, o, kWave);
-      if (os < best || (os == best && oi < best_id)) {
-        best = os;
-        best_id = oi;
-      }
-    }
+    wave_min_score_id(best, best_id);
     if (lane == 0) {
       sm.s_score[wave] = best;
       sm.s_id[wave] = best_id;
@@ -969,7 +977,7 @@ __global__ __launch_bounds__(THREADS) void row_kernel(const RowArgs a, const int
 }
 
 size_t lds_bytes_for(int n) {
-  if (n <= kDirectMaxN) return NBINS * sizeof(uint32_t) + kKeptCap * 8;
+  if (n <= kDirectMaxN) return NBINS * sizeof(uint32_t) + kKeptCap * 12;
   return static_cast<size_t>((n + 7) & ~7) * 2 + NBINS * sizeof(uint32_t) + kListCap * sizeof(uint16_t);
 }
 
