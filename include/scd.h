@@ -168,6 +168,13 @@ int scd_step(scd_ctx* ctx, const uint16_t* d_h, const uint16_t* d_W, void* d_sta
  * by the caller).  NULL, NULL turns it off.  Host-only call. */
 int scd_set_lm_head_events(scd_ctx* ctx, void* ev_start, void* ev_stop);
 
+/* For reports: writes the name of the LM-head kernel that scd_step / scd_lm_head launch
+ * for this context's sizes, e.g. "lm_head_splitk_kernel<1, 2, 8>" (template arguments:
+ * row blocks per workgroup, 1 + CFG, wavefronts), NUL-terminated, into host_buf[0..cap).
+ * Returns SCD_OK, or SCD_EINVAL (NULL argument, cfg.d == 0, or cap too small).
+ * Host-only call. */
+int scd_lm_head_kernel_name(scd_ctx* ctx, char* host_buf, size_t cap);
+
 /* The same iteration with the processed logits supplied by the caller
  * (d_z fp32 [B, L, n], window order) instead of computed by the LM head. */
 int scd_step_logits(scd_ctx* ctx, const float* d_z, void* d_state);

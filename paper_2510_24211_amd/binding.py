@@ -73,6 +73,7 @@ def load():
     lib.scd_step.argtypes = [vp, vp, vp, vp]
     lib.scd_step_logits.argtypes = [vp, vp, vp]
     lib.scd_set_lm_head_events.argtypes = [vp, vp, vp]
+    lib.scd_lm_head_kernel_name.argtypes = [vp, ctypes.c_char_p, sz]
     lib.scd_status.argtypes = [vp, vp, ctypes.POINTER(i32 * 4)]
     lib.scd_strerror.restype = ctypes.c_char_p
     lib.scd_strerror.argtypes = [ctypes.c_int]
@@ -80,7 +81,7 @@ def load():
     lib.scdw_copy.argtypes = [vp, vp, vp, sz]
     for name in ("scd_create", "scd_destroy", "scd_reset", "scd_state_field", "scd_lm_head",
                  "scd_select", "scd_couple_draft", "scd_verify", "scd_step", "scd_step_logits",
-                 "scd_set_lm_head_events",
+                 "scd_set_lm_head_events", "scd_lm_head_kernel_name",
                  "scd_status", "scdw_gather_hidden", "scdw_copy"):
         getattr(lib, name).restype = ctypes.c_int
     _lib = lib
@@ -225,6 +226,11 @@ class Scd:
         self._check(self.lib.scd_set_lm_head_events(
             self.ctx, ctypes.c_void_p(ev_start) if ev_start else None,
             ctypes.c_void_p(ev_stop) if ev_stop else None), "scd_set_lm_head_events")
+
+    def lm_head_kernel_name(self):
+        buf = ctypes.create_string_buffer(96)
+        self._check(self.lib.scd_lm_head_kernel_name(self.ctx, buf, 96), "scd_lm_head_kernel_name")
+        return buf.value.decode()
 
     def step_logits(self, z, state):
         c = self.cfg

@@ -32,6 +32,8 @@
 //     the end (a fixed order: deterministic).
 #include "scd_kernels.h"
 
+#include <stdio.h>
+
 namespace scd {
 namespace {
 
@@ -497,24 +499,46 @@ hipError_t launch_split(const LmHeadArgs& a, hipStream_t s) {
   return hipGetLastError();
 }
 
-template <int C>
-hipError_t launch_c(const LmHeadArgs& a, hipStream_t s) {
+// Which kernel serves a problem shape.
+struct Variant {
+  bool split;   // lm_head_splitk_kernel (else lm_head_kernel)
+  int rbw, nw;  // row blocks per workgroup; wavefronts (= k parts for the split kernel)
+};
+Variant choose(const LmHeadArgs& a) {
   const int nRB = a.B * ((a.L + 31) / 32);
   const int KT = (a.d + BK - 1) / BK;
   // Narrow vocabularies: with 128-column workgroups fewer than ~1.5 per CU would exist;
   // split k inside the workgroup instead and give every workgroup 32 columns.
   const bool narrow = (a.n + 127) / 128 < 384 && KT >= 16;
-  if (nRB >= 4) return launch_wide<4, C, 4>(a, s);
-  if (nRB >= 2) return narrow ? launch_split<2, C, 4>(a, s) : launch_wide<2, C, 4>(a, s);
-  if (narrow) return KT >= 48 ? launch_split<1, C, 8>(a, s) : launch_split<1, C, 4>(a, s);
+  if (nRB >= 4) return {false, 4, 4};
+  if (nRB >= 2) return {narrow, 2, 4};
+  if (narrow) return {true, 1, KT >= 48 ? 8 : 4};
   // wide vocabulary: 8 wavefronts share each h tile (halves the h traffic out of L2)
-  return (a.n + 255) / 256 >= 200 ? launch_wide<1, C, 8>(a, s) : launch_wide<1, C, 4>(a, s);
+  return {false, 1, (a.n + 255) / 256 >= 200 ? 8 : 4};
+}
+
+template <int C>
+hipError_t launch_c(const LmHeadArgs& a, hipStream_t s) {
+  const Variant v = choose(a);
+  if (v.split) {
+    if (v.rbw == 2) return launch_split<2, C, 4>(a, s);
+    return v.nw == 8 ? launch_split<1, C, 8>(a, s) : launch_split<1, C, 4>(a, s);
+  }
+  if (v.rbw == 4) return launch_wide<4, C, 4>(a, s);
+  if (v.rbw == 2) return launch_wide<2, C, 4>(a, s);
+  return v.nw == 8 ? launch_wide<1, C, 8>(a, s) : launch_wide<1, C, 4>(a, s);
 }
 
 }  // namespace
 
 hipError_t launch_lm_head(const LmHeadArgs& a, hipStream_t s) {
   return a.C == 2 ? launch_c<2>(a, s) : launch_c<1>(a, s);
+}
+
+int lm_head_kernel_name(const LmHeadArgs& a, char* buf, size_t cap) {
+  const Variant v = choose(a);
+  return snprintf(buf, cap, "%s<%d, %d, %d>", v.split ? "lm_head_splitk_kernel" : "lm_head_kernel",
+                  v.rbw, a.C, v.nw);
 }
 
 }  // namespace scd

@@ -357,6 +357,14 @@ int scd_set_lm_head_events(scd_ctx* c, void* ev_start, void* ev_stop) {
   return SCD_OK;
 }
 
+int scd_lm_head_kernel_name(scd_ctx* c, char* host_buf, size_t cap) {
+  if (!c || !host_buf || cap == 0 || c->cfg.d <= 0) return SCD_EINVAL;
+  scd::LmHeadArgs a{};
+  a.B = c->cfg.B; a.C = c->C; a.L = c->cfg.L; a.d = c->cfg.d; a.n = c->n;
+  const int len = scd::lm_head_kernel_name(a, host_buf, cap);
+  return (len < 0 || static_cast<size_t>(len) >= cap) ? SCD_EINVAL : SCD_OK;
+}
+
 int scd_step_logits(scd_ctx* c, const float* d_z, void* st) {
   if (!c || !d_z || !st || !aligned(st, kAlign)) return SCD_EINVAL;
   scd::CopyInArgs a{};

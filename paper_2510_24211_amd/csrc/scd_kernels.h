@@ -19,6 +19,9 @@ struct LmHeadArgs {
   float lam, one_plus_lam, tau;
 };
 hipError_t launch_lm_head(const LmHeadArgs& a, hipStream_t s);
+// Name (as a profiler prints it, without namespaces and arguments) of the kernel that
+// launch_lm_head picks for these sizes (only B, C, L, d, n are read); snprintf semantics.
+int lm_head_kernel_name(const LmHeadArgs& a, char* buf, size_t cap);
 
 // ---- top-k threshold + softmax normaliser -------------------------------
 struct SelectArgs {
