@@ -11,7 +11,9 @@ resident in HBM before the timed region starts; nothing crosses PCIe inside it.
 Prints ONE JSON line.  `value` = window positions verified per second over the
 timed steps; `tokens_per_s` = emitted tokens per second over the same steps.
 `roofline` describes the dominant kernel (the LM-head stream over W), timed with
-HIP events recorded inside scd_step on the stream it runs on.  `cpu_baseline`
+HIP events recorded inside scd_step on the stream it runs on, in a repeat of the
+timed steps (the events themselves slow a step by several microseconds, so `value`
+comes from the pass without them; `config.ms_per_step_with_events` is the other).  `cpu_baseline`
 is the NumPy oracle timed on the host cores on a bounded sample of the same
 workload.
 """
@@ -43,7 +45,10 @@ def parse():
                     help="profiling aid: skip the whole-decode warm-up, run --warmup then --steps "
                          "iterations from a fresh state (both must be given and fit in one decode)")
     ap.add_argument("--no-events", action="store_true",
-                    help="do not record the per-step LM-head events (roofline from a second pass)")
+                    help="do not record the per-step LM-head events (no roofline object)")
+    ap.add_argument("--events-in-step", action="store_true",
+                    help="record the LM-head events in the pass that gives `value` (default: in an "
+                         "identical second pass, because the events slow the step down)")
     ap.add_argument("--no-full-vocab", action="store_true",
                     help="C2 only: skip the companion measurement with all 65536 ids allowed")
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="MIB",
@@ -245,6 +250,9 @@ def measure(a, name, inputs):
 
     use_events = not a.no_events
     ev = HipEvents(K) if use_events else None
+    enqueue_us = []                               # host time per step to enqueue (first pass = value's)
+
+    hs = [h_of(i) for i in range(nfe)]            # views, made outside the timed loops
 
     def timed_pass(with_events):
         v0 = int(s.state_field(st, B.F_VERIFIED).sum().item())   # non-zero only after --quick warm-up
@@ -258,10 +266,12 @@ def measure(a, name, inputs):
                 done_decodes, in_decode = done_decodes + 1, 0
             if with_events:
                 s.set_lm_head_events(*ev.pair(i))
-            s.step(h_of(in_decode), W, st)
+            s.step(hs[in_decode], W, st)
             in_decode += 1
+        t_enq = time.perf_counter() - t0
         torch.cuda.synchronize()
         T = time.perf_counter() - t0
+        enqueue_us.append(t_enq / K * 1e6)
         if with_events:
             s.set_lm_head_events(None, None)
         verified = done_decodes * verified_per_decode - v0 + int(s.state_field(st, B.F_VERIFIED).sum().item())
@@ -270,7 +280,27 @@ def measure(a, name, inputs):
             assert torch.equal(s.state_field(st, B.F_OUT), tokens_ref), "decode is not reproducible"
         return T, verified, tokens
 
-    T, verified, tokens = timed_pass(use_events)
+    # The event pairs cost about 6 us per step (two more packets on the stream between the
+    # kernels), so the throughput comes from a pass without them and the LM-head timing from
+    # an identical pass with them, right after (--events-in-step: one pass for both).
+    T_ev = None
+    if use_events and not a.events_in_step:
+        T, verified, tokens = timed_pass(False)
+        if a.quick:                               # the second pass repeats the same steps
+            s.reset(st)
+            redo = 0
+            for i in range(Wm):
+                if redo == nfe:
+                    s.reset(st)
+                    redo = 0
+                s.step(h_of(redo), W, st)
+                redo += 1
+        else:
+            s.reset(st)
+        T_ev, _, _ = timed_pass(True)
+    else:
+        T, verified, tokens = timed_pass(use_events)
+        T_ev = T if use_events else None
     rc, flags = s.status(st)
     assert rc == B.SCD_OK
 
@@ -314,7 +344,10 @@ def measure(a, name, inputs):
                    "step_bytes_algorithmic": alg_bytes + 2 * w.B * w.L * min(n, w.top_k or n) * 8,
                    "step_hbm_frac": (alg_bytes + 2 * w.B * w.L * min(n, w.top_k or n) * 8)
                    / (T / K) / 1e9 / HBM_PEAK_GBS,
-                   "lm_head_events_in_timed_region": bool(use_events),
+                   "lm_head_events": ("none" if not use_events else "same pass as value"
+                                      if a.events_in_step else "repeat of the timed steps"),
+                   "ms_per_step_with_events": None if T_ev is None else T_ev / K * 1e3,
+                   "host_enqueue_us_per_step": enqueue_us[0],
                    "setup_s": t_setup},
         "roofline": roof,
     }
