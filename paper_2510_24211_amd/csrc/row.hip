@@ -386,10 +386,12 @@ struct RowOut {      // what a path hands to the common tail
 // Everything after the candidates sit in registers: threshold (if top-k filters),
 // normaliser, accept test, residual race.  Returns false if the threshold could not
 // be certified against `cut_max` (the caller then takes the complete path).
-// zq[e] is the previous iteration's logit of id vid[e] (read by the caller together with
-// zv, long before a rejection may need it; unused for a fresh position).  The LDS arrays
-// cid / cz / cq hold ccap entries each.
-template <int PER>
+// PREQ: zq[e] is the previous iteration's logit of id vid[e], read by the caller together
+// with zv (coalesced, long before a rejection may need it; unused for a fresh position).
+// Otherwise (ids scattered over the row) the previous logits of the KEPT ids are gathered
+// here, right after the compaction, so that the round trip hides behind the normaliser and
+// the accept draw.  The LDS arrays cid / cz / cq hold ccap entries each.
+template <int PER, bool PREQ>
 __device__ __forceinline__ bool finish_regs(const RowArgs& a, const RowRef& R, const int (&vid)[PER],
                                             const float (&zv)[PER], const float (&zq)[PER],
                                             const bool (&ok)[PER], bool filter, uint32_t cut_max,
@@ -428,21 +430,38 @@ __device__ __forceinline__ bool finish_regs(const RowArgs& a, const RowRef& R, c
   int Cn;
   int off = block_offsets(mine, Cn, sm);
   const bool compact = Cn <= ccap;
+  const bool want_q = a.mode != kRowSelectOnly && !R.fresh;
+  constexpr int KPT = kKeptCap / THREADS;   // ccap <= KPT * THREADS
+  int rid[KPT];
+  float rz[KPT], rq[KPT];
   if (compact) {
 #pragma unroll
     for (int e = 0; e < PER; ++e) {
       if (kept[e]) {
         cid[off] = static_cast<uint32_t>(vid[e]);
         cz[off] = zv[e];
-        cq[off] = zq[e];
+        if (PREQ) cq[off] = zq[e];
         ++off;
       }
     }
     __syncthreads();
+#pragma unroll
+    for (int q = 0; q < KPT; ++q) {
+      const int i = tid + q * THREADS;
+      rid[q] = i < Cn ? static_cast<int>(cid[i]) : -1;
+      rz[q] = i < Cn ? cz[i] : 0.f;
+      rq[q] = (PREQ && i < Cn) ? cq[i] : 0.f;
+    }
+    if (!PREQ && want_q) {                    // unpredicated gathers (id 0 where there is none)
+#pragma unroll
+      for (int q = 0; q < KPT; ++q) rq[q] = R.zp[rid[q] >= 0 ? rid[q] : 0];
+    }
   }
   float sum = 0.f;
   if (compact) {
-    for (int i = tid; i < Cn; i += THREADS) sum += expf(cz[i] - m);
+#pragma unroll
+    for (int q = 0; q < KPT; ++q)
+      if (rid[q] >= 0) sum += expf(rz[q] - m);
   } else {
 #pragma unroll
     for (int e = 0; e < PER; ++e)
@@ -490,16 +509,6 @@ __device__ __forceinline__ bool finish_regs(const RowArgs& a, const RowRef& R, c
   };
   if (compact) {
     // residuals r = p - q of the kept ids, then a second compaction of the positive ones
-    constexpr int KPT = kKeptCap / THREADS;   // ccap <= KPT * THREADS
-    int rid[KPT];
-    float rz[KPT], rq[KPT];
-#pragma unroll
-    for (int q = 0; q < KPT; ++q) {
-      const int i = tid + q * THREADS;
-      rid[q] = i < Cn ? static_cast<int>(cid[i]) : -1;
-      rz[q] = i < Cn ? cz[i] : 0.f;
-      rq[q] = i < Cn ? cq[i] : 0.f;
-    }
     int npos = 0;
 #pragma unroll
     for (int q = 0; q < KPT; ++q) {
@@ -525,11 +534,14 @@ __device__ __forceinline__ bool finish_regs(const RowArgs& a, const RowRef& R, c
     __syncthreads();
     for (int i = tid; i < ntot; i += THREADS) race_one(static_cast<int>(cid[i]), cz[i]);
   } else {
+    float zq2[PER];
+#pragma unroll
+    for (int e = 0; e < PER; ++e) zq2[e] = PREQ ? zq[e] : ((want_q && kept[e]) ? R.zp[vid[e]] : 0.f);
 #pragma unroll
     for (int e = 0; e < PER; ++e) {
       if (kept[e]) {
         const float pv = expf(zv[e] - lse_c);
-        const float qv = R.fresh ? q_uniform : prob(zq[e], R.thr_p, R.lse_p);
+        const float qv = R.fresh ? q_uniform : prob(zq2[e], R.thr_p, R.lse_p);
         const float rv = __fsub_rn(pv, qv);
         if (rv > 0.f) race_one(vid[e], rv);
       }
@@ -673,13 +685,12 @@ __device__ __forceinline__ void full_path(const RowArgs& a, const RowRef& R, uns
     }
 #pragma unroll
     for (int e = 0; e < PER_LIST; ++e) zv[e] = ok[e] ? zc[vid[e]] : 0.f;
-    float zq[PER_LIST];
-    const bool want_q = a.mode != kRowSelectOnly && !R.fresh;
+    float zq[PER_LIST];                        // unused: finish_regs gathers what it needs
 #pragma unroll
-    for (int e = 0; e < PER_LIST; ++e) zq[e] = (want_q && ok[e]) ? R.zp[vid[e]] : 0.f;
+    for (int e = 0; e < PER_LIST; ++e) zq[e] = 0.f;
     // the prefixes in LDS are spent: their space takes the compaction arrays
     const int ccap = min(kKeptCap, static_cast<int>(static_cast<size_t>(n8) * 2 / 12));
-    finish_regs<PER_LIST>(a, R, vid, zv, zq, ok, true, 0u, zcx, zpx, hist,
+    finish_regs<PER_LIST, false>(a, R, vid, zv, zq, ok, true, 0u, zcx, zpx, hist,
                           reinterpret_cast<uint32_t*>(smem), reinterpret_cast<float*>(smem) + ccap,
                           reinterpret_cast<float*>(smem) + 2 * ccap, ccap, sm, out);
     return;
@@ -815,7 +826,7 @@ __device__ __forceinline__ void direct_path(const RowArgs& a, const RowRef& R, u
     }
   }
   uint32_t* cid = hist + NBINS;
-  finish_regs<PER>(a, R, vid, zv, zq, ok, filter, 0u, zcx, zpx, hist, cid,
+  finish_regs<PER, true>(a, R, vid, zv, zq, ok, filter, 0u, zcx, zpx, hist, cid,
                    reinterpret_cast<float*>(cid + kKeptCap),
                    reinterpret_cast<float*>(cid + 2 * kKeptCap), kKeptCap, sm, out);
 }
@@ -854,18 +865,29 @@ __global__ __launch_bounds__(THREADS) void row_kernel(const RowArgs a, const int
   } else if (filter && a.cand && P > 0) {
     // ---- candidates emitted by the slice kernel ----------------------------------
     uint32_t* hist = reinterpret_cast<uint32_t*>(smem + static_cast<size_t>((n + 7) & ~7) * 2);
-    const uint32_t* cnt_in = a.cand_cnt + static_cast<size_t>(r) * 8;
-    const uint32_t* cut_in = a.cand_cut + static_cast<size_t>(r) * 8;
+    // The 8 slice counts and cuts of the row (two 16-byte loads each) and the candidate
+    // slots themselves are fetched in ONE round trip: slots are read whether filled or not
+    // (always inside the row's kListCap pairs) and masked by the counts afterwards.
+    const uint4* cnt4 = reinterpret_cast<const uint4*>(a.cand_cnt + static_cast<size_t>(r) * 8);
+    const uint4* cut4 = reinterpret_cast<const uint4*>(a.cand_cut + static_cast<size_t>(r) * 8);
+    const uint4 cA = cnt4[0], cB = cnt4[1], qA = cut4[0], qB = cut4[1];
+    const uint2* src = a.cand + static_cast<size_t>(r) * kListCap;
+    uint2 raw[PER_LIST];
+#pragma unroll
+    for (int e = 0; e < PER_LIST; ++e) raw[e] = src[tid + e * THREADS];
+    const uint32_t cnt8[8] = {cA.x, cA.y, cA.z, cA.w, cB.x, cB.y, cB.z, cB.w};
+    const uint32_t cut8[8] = {qA.x, qA.y, qA.z, qA.w, qB.x, qB.y, qB.z, qB.w};
     bool fits = true;
     uint32_t cut_max = 0, total = 0;
-    for (int p = 0; p < P; ++p) {
-      const uint32_t c = cnt_in[p], q = cut_in[p];
-      fits &= c <= static_cast<uint32_t>(capE);
-      total += c;
-      cut_max = q > cut_max ? q : cut_max;
+#pragma unroll
+    for (int p = 0; p < 8; ++p) {
+      if (p < P) {
+        fits &= cnt8[p] <= static_cast<uint32_t>(capE);
+        total += cnt8[p];
+        cut_max = cut8[p] > cut_max ? cut8[p] : cut_max;
+      }
     }
     if (fits && total >= static_cast<uint32_t>(a.top_k)) {
-      const uint2* src = a.cand + static_cast<size_t>(r) * kListCap;
       int vid[PER_LIST];
       float zv[PER_LIST];
       bool ok[PER_LIST];
@@ -873,18 +895,18 @@ __global__ __launch_bounds__(THREADS) void row_kernel(const RowArgs a, const int
       for (int e = 0; e < PER_LIST; ++e) {
         const int i = tid + e * THREADS;
         const int p = i / capE, o = i - p * capE;
-        ok[e] = p < P && static_cast<uint32_t>(o) < cnt_in[p];
-        const uint2 t = ok[e] ? src[i] : make_uint2(0u, 0u);
-        vid[e] = static_cast<int>(t.x);
-        zv[e] = __uint_as_float(t.y);
-      }
-      float zq[PER_LIST];
-      const bool want_q = a.mode != kRowSelectOnly && !R.fresh;
+        uint32_t c = 0;
 #pragma unroll
-      for (int e = 0; e < PER_LIST; ++e)
-        zq[e] = (want_q && ok[e]) ? R.zp[vid[e]] : 0.f;
+        for (int pp = 0; pp < 8; ++pp) c = (pp == p && pp < P) ? cnt8[pp] : c;
+        ok[e] = static_cast<uint32_t>(o) < c && raw[e].x < static_cast<uint32_t>(n);
+        vid[e] = ok[e] ? static_cast<int>(raw[e].x) : 0;
+        zv[e] = ok[e] ? __uint_as_float(raw[e].y) : 0.f;
+      }
+      float zq[PER_LIST];                      // unused: finish_regs gathers what it needs
+#pragma unroll
+      for (int e = 0; e < PER_LIST; ++e) zq[e] = 0.f;
       const int ccap = min(kKeptCap, static_cast<int>(static_cast<size_t>((n + 7) & ~7) * 2 / 12));
-      done = finish_regs<PER_LIST>(a, R, vid, zv, zq, ok, true, cut_max, zcx, zpx, hist,
+      done = finish_regs<PER_LIST, false>(a, R, vid, zv, zq, ok, true, cut_max, zcx, zpx, hist,
                                    reinterpret_cast<uint32_t*>(smem), reinterpret_cast<float*>(smem) + ccap,
                                    reinterpret_cast<float*>(smem) + 2 * ccap, ccap, sm, out);
     }
