@@ -65,6 +65,8 @@ struct Small {
   int ired[NW];
   uint32_t wtot[NW];
   uint32_t sel_bin, sel_above;
+  uint32_t cursor;        // append cursor of select_regs
+  int ired2[NW];          // second slot of block_offsets
   float s_score[NW];
   int s_id[NW];
   int last;
@@ -76,7 +78,10 @@ __device__ __forceinline__ uint32_t zkey(float f) { return float_to_key(f == 0.f
 
 // hist[0..NBINS): find the bin holding the `need`-th largest element counting
 // from the top bin; lowers `need` by the population of the bins above it.
-__device__ __forceinline__ uint32_t find_bin(const uint32_t* hist, uint32_t& need, Small& sm) {
+// The trailing barrier keeps a later writer of sel_bin / sel_above / wtot away from slow
+// readers; a caller whose next such write comes after another barrier anyway may drop it.
+__device__ __forceinline__ uint32_t find_bin(const uint32_t* hist, uint32_t& need, Small& sm,
+                                             bool trailing = true) {
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   constexpr int PER = NBINS / THREADS;   // 4 consecutive bins per thread, top bins in thread 0
   uint32_t c[PER], local = 0;
@@ -107,7 +112,7 @@ __device__ __forceinline__ uint32_t find_bin(const uint32_t* hist, uint32_t& nee
   __syncthreads();
   const uint32_t bin = sm.sel_bin;
   need -= sm.sel_above;
-  __syncthreads();
+  if (trailing) __syncthreads();
   return bin;
 }
 
@@ -121,24 +126,29 @@ __device__ __forceinline__ float prob(float z, float thr, float lse) {
 }
 
 // Exclusive offset of this thread's `cnt` in a fixed thread order, and the total.
-__device__ __forceinline__ int block_offsets(int cnt, int& total, Small& sm) {
+// `slot` picks one of two exchange arrays; without the trailing barrier the caller must
+// have another barrier between this call and the next one on the same slot.
+__device__ __forceinline__ int block_offsets(int cnt, int& total, Small& sm, int slot = 0,
+                                             bool trailing = true) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int incl = wave_inclusive_sum_i32(cnt, lane);
-  if (lane == 63) sm.ired[wave] = incl;
+  int* const ex = slot ? sm.ired2 : sm.ired;
+  if (lane == 63) ex[wave] = incl;
   __syncthreads();
   int base = 0;
   total = 0;
 #pragma unroll
   for (int w = 0; w < NW; ++w) {
-    base += w < wave ? sm.ired[w] : 0;
-    total += sm.ired[w];
+    base += w < wave ? ex[w] : 0;
+    total += ex[w];
   }
-  __syncthreads();
+  if (trailing) __syncthreads();
   return base + incl - cnt;
 }
 
 // max / min of keys over the workgroup
-__device__ __forceinline__ void block_minmax(uint32_t& kmin, uint32_t& kmax, Small& sm) {
+__device__ __forceinline__ void block_minmax(uint32_t& kmin, uint32_t& kmax, Small& sm,
+                                             bool trailing = true) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   kmax = wave_max_u32(kmax);
   kmin = ~wave_max_u32(~kmin);
@@ -152,7 +162,7 @@ __device__ __forceinline__ void block_minmax(uint32_t& kmin, uint32_t& kmax, Sma
     kmax = sm.umax[w] > kmax ? sm.umax[w] : kmax;
     kmin = sm.umin[w] < kmin ? sm.umin[w] : kmin;
   }
-  __syncthreads();
+  if (trailing) __syncthreads();
 }
 
 // `need`-th largest key among the register-resident logits zv[e] (keys kv[e], valid
@@ -170,7 +180,9 @@ template <int PER>
 __device__ __forceinline__ uint32_t select_regs(const float (&zv)[PER], const uint32_t (&kv)[PER],
                                                 const bool (&ok)[PER], uint32_t kmin_in,
                                                 uint32_t kmax, uint32_t need, uint32_t* hist,
-                                                Small& sm) {
+                                                uint32_t* arr, Small& sm) {
+  // hist was zeroed by the caller before the barrier of block_minmax; arr (NBINS entries,
+  // disjoint from hist) takes the members of the selected bin.
   const float zlo = key_to_float(kmin_in), zhi = key_to_float(kmax);
   const float scale = (zhi > zlo) ? __fdiv_rn(static_cast<float>(NBINS - 1), zhi - zlo) : 0.f;
   int bin[PER];
@@ -183,21 +195,18 @@ __device__ __forceinline__ uint32_t select_regs(const float (&zv)[PER], const ui
     }
     bin[e] = bb;
   }
-  zero_hist(hist);
-  __syncthreads();
+  if (threadIdx.x == 0) sm.cursor = 0u;          // append cursor, published by the next barrier
 #pragma unroll
   for (int e = 0; e < PER; ++e)
     if (ok[e]) atomicAdd(&hist[bin[e]], 1u);
   __syncthreads();
-  const int b1 = static_cast<int>(find_bin(hist, need, sm));
+  // no trailing barrier: sel_bin is next written after the barrier that follows the append
+  const int b1 = static_cast<int>(find_bin(hist, need, sm, false));
   const uint32_t members = hist[b1];
-  if (threadIdx.x == 0) sm.sel_above = 0u;       // append cursor
-  __syncthreads();
   if (members <= static_cast<uint32_t>(NBINS)) {
-    uint32_t* arr = hist;                        // the histogram is spent: reuse it for the keys
 #pragma unroll
     for (int e = 0; e < PER; ++e)
-      if (ok[e] && bin[e] == b1) arr[atomicAdd(&sm.sel_above, 1u)] = kv[e];
+      if (ok[e] && bin[e] == b1) arr[atomicAdd(&sm.cursor, 1u)] = kv[e];
     __syncthreads();
 #pragma unroll
     for (int e = 0; e < PER; ++e) {
@@ -212,10 +221,9 @@ __device__ __forceinline__ uint32_t select_regs(const float (&zv)[PER], const ui
       }
     }
     __syncthreads();
-    const uint32_t res = sm.sel_bin;
-    __syncthreads();
-    return res;
+    return sm.sel_bin;      // its next writer sits behind the barriers of the caller's next step
   }
+  __syncthreads();          // every thread has read hist[b1] before the histogram is reused
   // radix levels over the key bits of the members, range [lo, lo + width)
   uint32_t lo = 0;
   uint64_t width = 1ull << 32;
@@ -302,6 +310,7 @@ __device__ __forceinline__ RowRef locate_row(const RowArgs& a, int r) {
 __global__ __launch_bounds__(THREADS) void slice_kernel(const RowArgs a, const int P, const int capE,
                                                         const int rank) {
   __shared__ uint32_t hist[NBINS];
+  __shared__ uint32_t arr[NBINS];
   __shared__ Small sm;
   const int tid = threadIdx.x;
   const int r = blockIdx.x / P, p = blockIdx.x % P;
@@ -350,15 +359,17 @@ __global__ __launch_bounds__(THREADS) void slice_kernel(const RowArgs a, const i
       if (zv[e] != zv[e] && a.flags) atomicOr(a.flags, 1);     // NaN of either sign
     }
   }
-  block_minmax(kmin, kmax, sm);
+  zero_hist(hist);                        // published by the barrier inside block_minmax
+  block_minmax(kmin, kmax, sm, false);
   const int nvalid = hi_id - lo_id;
   uint32_t cut = 0;                       // 0: the whole slice is emitted
-  if (nvalid > rank) cut = select_regs<PER_SLICE>(zv, kv, ok, kmin, kmax, static_cast<uint32_t>(rank), hist, sm);
+  if (nvalid > rank)
+    cut = select_regs<PER_SLICE>(zv, kv, ok, kmin, kmax, static_cast<uint32_t>(rank), hist, arr, sm);
   int mine = 0;
 #pragma unroll
   for (int e = 0; e < PER_SLICE; ++e) mine += (ok[e] && kv[e] >= cut) ? 1 : 0;
   int total;
-  int off = block_offsets(mine, total, sm);
+  int off = block_offsets(mine, total, sm, 0, false);
   uint2* const dst = a.cand + (static_cast<size_t>(r) * kListCap + static_cast<size_t>(p) * capE);
 #pragma unroll
   for (int e = 0; e < PER_SLICE; ++e) {
@@ -409,11 +420,14 @@ __device__ __forceinline__ bool finish_regs(const RowArgs& a, const RowRef& R, c
       if (zv[e] != zv[e] && a.flags) atomicOr(a.flags, 1);     // NaN of either sign
     }
   }
-  block_minmax(kmin, kmax, sm);
+  if (filter) zero_hist(hist);            // published by the barrier inside block_minmax
+  block_minmax(kmin, kmax, sm, false);
   const float m = key_to_float(kmax);
   float thr = -INFINITY;
   if (filter) {
-    const uint32_t tkey = select_regs<PER>(zv, kv, ok, kmin, kmax, static_cast<uint32_t>(a.top_k), hist, sm);
+    // cid (ccap entries, all of them free until the compaction) takes the selected bin's members
+    const uint32_t tkey = select_regs<PER>(zv, kv, ok, kmin, kmax, static_cast<uint32_t>(a.top_k), hist,
+                                           cid, sm);
     if (tkey < cut_max) return false;     // an unseen logit could be >= the K-th candidate
     thr = key_to_float(tkey);
   }
@@ -428,7 +442,7 @@ __device__ __forceinline__ bool finish_regs(const RowArgs& a, const RowRef& R, c
     mine += kept[e] ? 1 : 0;
   }
   int Cn;
-  int off = block_offsets(mine, Cn, sm);
+  int off = block_offsets(mine, Cn, sm, 0, false);   // next barrier: after the compaction / in the sum
   const bool compact = Cn <= ccap;
   const bool want_q = a.mode != kRowSelectOnly && !R.fresh;
   constexpr int KPT = kKeptCap / THREADS;   // ccap <= KPT * THREADS
@@ -522,7 +536,7 @@ __device__ __forceinline__ bool finish_regs(const RowArgs& a, const RowRef& R, c
       npos += rv > 0.f ? 1 : 0;
     }
     int ntot;
-    int o2 = block_offsets(npos, ntot, sm);        // its barriers also end every read of cid / cz
+    int o2 = block_offsets(npos, ntot, sm, 1, false);   // cid / cz were read before the sum's barrier
 #pragma unroll
     for (int q = 0; q < KPT; ++q) {
       if (rz[q] > 0.f) {
