@@ -10,5 +10,6 @@ Modules
   philox   counter-based Philox4x32-10 generator and the uniform mapping
   logits   LM head (fp64), CFG combine, id mask, temperature, top-k, softmax
   mrs      Modified Rejection Sampling (accept test + residual resample)
+  gs       Gumbel-sharing coupling (shared-noise Gumbel-max draws)
   scd      the SCD decode loop in its vectorised and its sequential form
 """

@@ -27,6 +27,7 @@ SH32 = np.uint64(32)
 STREAM_INIT = 0    # initial draft token of a never-evaluated position
 STREAM_ACCEPT = 1  # the uniform of the accept test
 STREAM_RESID = 2   # one uniform per vocab id for the residual race
+STREAM_GUMBEL = 3  # one uniform per vocab id for the shared Gumbel noise of a position
 
 
 def philox4x32_10(c0, c1, c2, c3, k0, k1):

@@ -1,5 +1,6 @@
-"""Speculative Coupled Decoding, maximal-coupling variant (oracle side; test
-infrastructure only).
+"""Speculative Coupled Decoding (oracle side; test infrastructure only): the
+maximal-coupling variant pi_MC and, with ScdConfig.coupling = "gs", the
+Gumbel-sharing variant pi_GS.
 
 Two forms of the same decode loop are written out:
 
@@ -27,6 +28,19 @@ Readings fixed here (the paper's loops are ambiguous about them):
     produced the target distribution P of that MRS call;
   * tokens are handled as offsets 0..|A|-1 into the allowed id range
     [v_lo, v_hi); emitted tokens are v_lo + offset.
+
+pi_GS (Alg. SCD(pi_GS) of the appendix "Algorithms"): the verification is the
+same sequence of MRS calls up to the first rejection; what changes is the
+redraft of the positions right of it, which is the shared-noise Gumbel-max draw
+from the position's newest distribution, X_j = argmax_v(log p_j(v) + G_j(v)),
+with G_j a function of the position only.  Further readings for it:
+  * a never-evaluated position gets its first draft exactly as under pi_MC (one
+    uniform draw from its own stream): its "Random()" distribution is uniform,
+    any draw from it is admissible, and this one costs one random number instead
+    of one per vocabulary id;
+  * the vectorised form evaluates the MRS call of every window position (the
+    calls right of the first rejection are discarded) and the Gumbel draw of
+    every window position (the draws left of it are discarded).
 """
 from dataclasses import dataclass, field
 import numpy as np
@@ -34,6 +48,7 @@ import numpy as np
 from . import philox
 from . import logits as lg
 from . import mrs as mrs_mod
+from . import gs as gs_mod
 
 
 @dataclass
@@ -48,10 +63,12 @@ class ScdConfig:
     temperature: float = 1.0
     cfg_lambda: float = 0.0  # 0 => no CFG
     seed: int = 0
+    coupling: str = "mc"     # "mc": maximal coupling (MRS redraft); "gs": Gumbel sharing
 
     def __post_init__(self):
         if self.v_hi < 0:
             self.v_hi = self.V
+        assert self.coupling in ("mc", "gs")
 
     @property
     def n_allowed(self):
@@ -145,9 +162,11 @@ class ScdOracle:
         return plan
 
     # -- phase 2: one MRS per window position ------------------------------
-    def sample(self, plan, accept_override=None, resid_override=None):
-        """Vectorised MRS (Alg. SCD(pi_MC), the parallel-for over the window).
-        Overrides force a decision and are legal only on flagged draws."""
+    def sample(self, plan, accept_override=None, resid_override=None, gs_override=None):
+        """Vectorised MRS (Alg. SCD(pi_MC), the parallel-for over the window); under
+        pi_GS also the Gumbel draw g of every window position (Alg. SCD(pi_GS),
+        "fixed noise sampling").  Overrides force a decision and are legal only on
+        flagged draws."""
         cfg = self.cfg
         res = []
         for b in range(cfg.B):
@@ -178,6 +197,15 @@ class ScdOracle:
                         and resid_override[key] != r["y"]:
                     assert r["flag_resid"], "residual override on an unflagged draw"
                     r["y"] = int(resid_override[key])
+                if cfg.coupling == "gs":
+                    Ug = philox.uniform_per_vocab(cfg.seed, b, j, 0, philox.STREAM_GUMBEL,
+                                                  cfg.n_allowed)
+                    g, _ = gs_mod.draw(p, Ug)
+                    r["flag_gs"] = gs_mod.flag(p, Ug, g, self.tol)
+                    if gs_override and key in gs_override and gs_override[key] != g:
+                        assert r["flag_gs"], "Gumbel override on an unflagged draw"
+                        g = int(gs_override[key])
+                    r["g"] = g
                 rows.append(r)
             res.append(rows)
         return res
@@ -201,7 +229,7 @@ class ScdOracle:
                 self.out[b, i + s] = cfg.v_lo + res[b][s]["y"]
             for s in range(a, Lw):                    # survivors: coupled redraft
                 j = i + s
-                self.X[b, j] = res[b][s]["y"]
+                self.X[b, j] = res[b][s]["g" if cfg.coupling == "gs" else "y"]
                 self.q[b][j] = plan[b][s]["p"]
                 self.age[b, j] += 1
             for s in range(a):                        # retired positions
@@ -263,11 +291,15 @@ def decode_sequential(cfg: ScdConfig, model, tol=1e-5):
             # been used on them yet (positions right of the last rejection).
             for j in range(i, i + Lw):
                 if j in p_new:
-                    u = philox.uniform_scalar(cfg.seed, b, j, t_new[j], philox.STREAM_ACCEPT)
-                    U_fn = lambda j=j: philox.uniform_per_vocab(
-                        cfg.seed, b, j, t_new[j], philox.STREAM_RESID, n)
-                    r = mrs_mod.mrs(p_new[j], p_old.get(j, uniform), X[j], u, U_fn, tol)
-                    X[j] = r["y"]
+                    if cfg.coupling == "gs":
+                        Ug = philox.uniform_per_vocab(cfg.seed, b, j, 0, philox.STREAM_GUMBEL, n)
+                        X[j] = gs_mod.draw(p_new[j], Ug)[0]
+                    else:
+                        u = philox.uniform_scalar(cfg.seed, b, j, t_new[j], philox.STREAM_ACCEPT)
+                        U_fn = lambda j=j: philox.uniform_per_vocab(
+                            cfg.seed, b, j, t_new[j], philox.STREAM_RESID, n)
+                        r = mrs_mod.mrs(p_new[j], p_old.get(j, uniform), X[j], u, U_fn, tol)
+                        X[j] = r["y"]
                     p_old[j] = p_new.pop(j)
             # Evaluate
             toks = np.array([out[b, j] - cfg.v_lo for j in range(i)] +
