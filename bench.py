@@ -39,6 +39,8 @@ def parse():
     ap.add_argument("--warmup", type=int, default=0, help="untimed steps; 0 = one whole decode")
     ap.add_argument("--workload", default="C2",
                     help="C1 | C2 | C2-fullV | C3 | C4 (see paper_2510_24211_amd/workload.py)")
+    ap.add_argument("--coupling", default="mc", choices=["mc", "gs"],
+                    help="mc: maximal coupling (the paper's pi_MC, default); gs: Gumbel sharing (pi_GS)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=15.0)
     ap.add_argument("--quick", action="store_true",
@@ -86,7 +88,7 @@ class HipEvents:
             self.hip.hipEventDestroy(e)
 
 
-def cpu_baseline(w, seconds):
+def cpu_baseline(w, seconds, coupling="mc"):
     """The oracle as it stands, on the host cores, for about `seconds` (whole decodes are
     repeated until the time is up; the last one may be cut short)."""
     import numpy as np
@@ -103,7 +105,8 @@ def cpu_baseline(w, seconds):
     del W
     tab = wl.HiddenTable(w)
     cfg = oscd.ScdConfig(B=w.B, L=w.L, N=w.N, V=w.V, v_lo=w.v_lo, v_hi=w.v_hi, top_k=w.top_k,
-                         temperature=w.temperature, cfg_lambda=w.cfg_lambda, seed=w.seed)
+                         temperature=w.temperature, cfg_lambda=w.cfg_lambda, seed=w.seed,
+                         coupling=coupling)
     o = oscd.ScdOracle(cfg)
     tab.window(list(o.i), [[0] * w.L for _ in range(w.B)])      # warm the generator caches
     t_in = 0.0
@@ -172,7 +175,7 @@ def main():
                                                          "ms_per_step", "config", "roofline")}
     inputs.clear()
     if not a.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(w, a.cpu_seconds)
+        out["cpu_baseline"] = cpu_baseline(w, a.cpu_seconds, a.coupling)
     print(json.dumps(out))
 
 
@@ -197,7 +200,9 @@ def measure(a, name, inputs):
         inputs.clear()
         inputs.update(key=key, W=to_dev(wl.lm_head_weight(w)), table=to_dev(wl.HiddenTable(w).full()))
     W, table = inputs["W"], inputs["table"]
-    s = B.Scd(B.config_from_workload(w), dev)
+    cfg = B.config_from_workload(w)
+    cfg.coupling = B.COUPLING_GS if a.coupling == "gs" else B.COUPLING_MC
+    s = B.Scd(cfg, dev)
     st = s.alloc_state()
     h = torch.empty((w.B, w.C, w.L, w.d), dtype=torch.bfloat16, device=dev)
     t_setup = time.perf_counter() - t_setup
@@ -345,7 +350,8 @@ def measure(a, name, inputs):
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": f"{w.name}: B={w.B} CFG={'on' if w.C == 2 else 'off'} L={w.L} "
                                f"N={w.N} V={w.V} allowed={n} d={w.d} top_k={w.top_k} "
-                               f"lambda={w.cfg_lambda} seed={w.seed} (synthetic drift model)",
+                               f"lambda={w.cfg_lambda} seed={w.seed} coupling={a.coupling} "
+                               f"(synthetic drift model)",
                    "decode_iterations": None if a.quick else int(nfe),
                    "tokens_per_iteration": None if a.quick else w.B * w.N / nfe,
                    "step_bytes_algorithmic": alg_bytes + 2 * w.B * w.L * min(n, w.top_k or n) * 8,

@@ -19,6 +19,12 @@
  *   4. first rejection r: emit y[0..a), a = min(r + 1, Lw) (a = Lw if none);
  *      the y right of r are the coupled redraft = next iteration's drafts;
  *      slide the window by a and give the entering positions uniform drafts.
+ * With coupling = SCD_COUPLING_GS (Alg. "GS(P, Q, G)", appendix Alg. SCD(pi_GS)) steps 1-3
+ * and the emission are the same; the redraft of the positions right of r is instead the
+ * shared-noise Gumbel-max draw from the position's new distribution,
+ *        g = argmax_v (log p(v) + G_j(v)),  G_j(v) = -ln(-ln U_j(v)),
+ * with noise that depends on the position j (and the id v) only, not on the iteration,
+ * decided as the equivalent exponential race argmin_v -ln(U_j(v)) / p(v) in fp32.
  *
  * Conventions
  *   - Every pointer named d_* is a DEVICE pointer owned by the caller.  The
@@ -37,7 +43,8 @@
  *   - Random numbers: Philox4x32-10, key = (seed low 32, seed high 32),
  *     counter = (vocab offset >> 2 or 0, position, iteration, b << 8 | stream),
  *     lane = vocab offset & 3 (lane 0 for scalar draws); streams 0 = initial
- *     draft, 1 = accept uniform, 2 = residual race.
+ *     draft, 1 = accept uniform, 2 = residual race, 3 = Gumbel noise (iteration
+ *     word 0).
  *     u = ((bits >> 9) + 0.5) * 2^-23.
  */
 #ifndef SCD_H
@@ -62,10 +69,16 @@ typedef struct scd_config {
   int32_t top_k;       /* 0 => off; K = min(top_k, n)                               */
   float temperature;   /* tau > 0                                                   */
   float cfg_lambda;    /* 0 => no guidance (C = 1); else C = 2, z = (1+l)c - l u    */
-  int32_t coupling;    /* 0 = maximal coupling (MRS); others not implemented        */
+  int32_t coupling;    /* scd_coupling: 0 = maximal coupling (MRS), 1 = Gumbel sharing */
   int32_t reserved;    /* must be 0                                                 */
   uint64_t seed;
 } scd_config;
+
+typedef enum scd_coupling {
+  SCD_COUPLING_MC = 0,   /* survivors' next drafts = their MRS outputs (Sec. 4.1)            */
+  SCD_COUPLING_GS = 1    /* survivors' next drafts = shared-noise Gumbel-max draws; needs
+                            v_hi - v_lo <= 65536                                             */
+} scd_coupling;
 
 typedef enum scd_error {
   SCD_OK = 0,
@@ -95,7 +108,9 @@ typedef enum scd_field {
   SCD_F_FLAGS = 14,   /* int32 [4]       [0] numeric-fault bits                        */
   SCD_F_VERIFIED = 15,/* int32 [B]       window positions verified so far (sum of Lw)  */
   SCD_F_TICKET = 16,  /* int32 [B]       internal arrival counters, zero between steps */
-  SCD_F_COUNT = 17
+  SCD_F_G = 17,       /* int32 [B, L]    last step's Gumbel-sharing draws, window order
+                                         (written under SCD_COUPLING_GS only)          */
+  SCD_F_COUNT = 18
 } scd_field;
 
 /* Bytes of caller-provided device scratch a context needs; 0 on a bad config. */

@@ -17,14 +17,15 @@ SCD_OK, SCD_EINVAL, SCD_EWORKSPACE, SCD_EHIP, SCD_ENUMERIC, SCD_EUNSUPPORTED = 0
 
 # scd_field
 (F_POS, F_ITER, F_X, F_AGE, F_OUT, F_ACCEPT, F_Y, F_K, F_PX, F_QX, F_THR, F_LSE, F_NKEPT, F_Z,
- F_FLAGS, F_VERIFIED, F_TICKET) = range(17)
+ F_FLAGS, F_VERIFIED, F_TICKET, F_G) = range(18)
+COUPLING_MC, COUPLING_GS = 0, 1
 
 _FIELD_DTYPE = {
     F_POS: torch.int32, F_ITER: torch.int32, F_X: torch.int32, F_AGE: torch.int32,
     F_OUT: torch.int32, F_ACCEPT: torch.int32, F_Y: torch.int32, F_K: torch.uint8,
     F_PX: torch.float32, F_QX: torch.float32, F_THR: torch.float32, F_LSE: torch.float32,
     F_NKEPT: torch.int32, F_Z: torch.float32, F_FLAGS: torch.int32, F_VERIFIED: torch.int32,
-    F_TICKET: torch.int32,
+    F_TICKET: torch.int32, F_G: torch.int32,
 }
 
 

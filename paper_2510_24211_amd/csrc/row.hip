@@ -390,9 +390,27 @@ __global__ __launch_bounds__(THREADS) void slice_kernel(const RowArgs a, const i
 struct RowOut {      // what a path hands to the common tail
   bool accept;
   float px, qx;
-  float best;
+  float best;         // residual race (on rejection)
   int best_id;
+  float gbest;        // Gumbel-sharing draft (GS kernels only)
+  int gbest_id;
 };
+
+// Entry of id v, probability pv > 0, in the shared-noise Gumbel-max draw of position j
+// (Alg. GS / Alg. SCD(pi_GS)): argmax_v(log p_v + G_v) with G_v = -ln(-ln U_v) is the
+// argmin of -ln(U_v) / p_v (appendix proof of the Gumbel-coupling theorem).  U_v is keyed by
+// (seed, sequence, position, id) only -- not by the iteration -- so that every iteration
+// redraws the position with the same noise.  Ties go to the lowest id.
+__device__ __forceinline__ void gumbel_entry(RowOut& out, uint2 key, uint32_t w3, int j, int v, float pv) {
+  const uint4 rr = philox4x32_10(make_uint4(static_cast<uint32_t>(v >> 2), static_cast<uint32_t>(j), 0u,
+                                            w3 | kStreamGumbel), key);
+  const uint32_t lanes[4] = {rr.x, rr.y, rr.z, rr.w};
+  const float sc = __fdiv_rn(-logf(u01(lanes[v & 3])), pv);
+  if (sc < out.gbest || (sc == out.gbest && v < out.gbest_id)) {
+    out.gbest = sc;
+    out.gbest_id = v;
+  }
+}
 
 // Everything after the candidates sit in registers: threshold (if top-k filters),
 // normaliser, accept test, residual race.  Returns false if the threshold could not
@@ -402,7 +420,7 @@ struct RowOut {      // what a path hands to the common tail
 // Otherwise (ids scattered over the row) the previous logits of the KEPT ids are gathered
 // here, right after the compaction, so that the round trip hides behind the normaliser and
 // the accept draw.  The LDS arrays cid / cz / cq hold ccap entries each.
-template <int PER, bool PREQ>
+template <int PER, bool PREQ, bool GS>
 __device__ __forceinline__ bool finish_regs(const RowArgs& a, const RowRef& R, const int (&vid)[PER],
                                             const float (&zv)[PER], const float (&zq)[PER],
                                             const bool (&ok)[PER], bool filter, uint32_t cut_max,
@@ -509,6 +527,25 @@ __device__ __forceinline__ bool finish_regs(const RowArgs& a, const RowRef& R, c
   out.accept = __fmul_rn(u01(ra.x), out.qx) <= out.px;
   out.best = INFINITY;
   out.best_id = 0x7FFFFFFF;
+  out.gbest = INFINITY;
+  out.gbest_id = 0x7FFFFFFF;
+  if (GS) {                        // every row: next draft should the row survive
+    if (compact) {
+#pragma unroll
+      for (int q = 0; q < KPT; ++q)
+        if (rid[q] >= 0) {
+          const float pv = expf(rz[q] - lse_c);
+          if (pv > 0.f) gumbel_entry(out, key, w3, j, rid[q], pv);
+        }
+    } else {
+#pragma unroll
+      for (int e = 0; e < PER; ++e)
+        if (kept[e]) {
+          const float pv = expf(zv[e] - lse_c);
+          if (pv > 0.f) gumbel_entry(out, key, w3, j, vid[e], pv);
+        }
+    }
+  }
   if (out.accept) return true;     // uniform over the workgroup
 
   auto race_one = [&](int v, float rv) {   // exponential-race entry of id v, residual rv > 0
@@ -567,6 +604,7 @@ __device__ __forceinline__ bool finish_regs(const RowArgs& a, const RowRef& R, c
 // The complete in-place path: one coalesced read of the row, 16-bit key prefixes in
 // LDS, histogram select; then a candidate list in registers, or in-place scans when
 // top-k is off or the candidates do not fit.
+template <bool GS>
 __device__ __forceinline__ void full_path(const RowArgs& a, const RowRef& R, unsigned char* smem,
                                           float zcx, float zpx, Small& sm, RowOut& out) {
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -704,7 +742,7 @@ __device__ __forceinline__ void full_path(const RowArgs& a, const RowRef& R, uns
     for (int e = 0; e < PER_LIST; ++e) zq[e] = 0.f;
     // the prefixes in LDS are spent: their space takes the compaction arrays
     const int ccap = min(kKeptCap, static_cast<int>(static_cast<size_t>(n8) * 2 / 12));
-    finish_regs<PER_LIST, false>(a, R, vid, zv, zq, ok, true, 0u, zcx, zpx, hist,
+    finish_regs<PER_LIST, false, GS>(a, R, vid, zv, zq, ok, true, 0u, zcx, zpx, hist,
                           reinterpret_cast<uint32_t*>(smem), reinterpret_cast<float*>(smem) + ccap,
                           reinterpret_cast<float*>(smem) + 2 * ccap, ccap, sm, out);
     return;
@@ -785,6 +823,14 @@ __device__ __forceinline__ void full_path(const RowArgs& a, const RowRef& R, uns
   out.accept = __fmul_rn(u01(ra.x), out.qx) <= out.px;
   out.best = INFINITY;
   out.best_id = 0x7FFFFFFF;
+  out.gbest = INFINITY;
+  out.gbest_id = 0x7FFFFFFF;
+  if (GS) {
+    for_each_candidate([&](int v, uint32_t) {
+      const float pv = prob(zc[v], thr, lse_c);
+      if (pv > 0.f) gumbel_entry(out, key, w3, j, v, pv);
+    });
+  }
   if (!out.accept) {
     for_each_candidate([&](int v, uint32_t) {
       const float pv = prob(zc[v], thr, lse_c);
@@ -807,7 +853,7 @@ __device__ __forceinline__ void full_path(const RowArgs& a, const RowRef& R, uns
 }
 
 // The whole row in registers, PER logits per thread (n <= PER * THREADS).
-template <int PER>
+template <int PER, bool GS>
 __device__ __forceinline__ void direct_path(const RowArgs& a, const RowRef& R, unsigned char* smem,
                                             bool filter, float zcx, float zpx, Small& sm, RowOut& out) {
   const int tid = threadIdx.x, n = a.n;
@@ -840,11 +886,12 @@ __device__ __forceinline__ void direct_path(const RowArgs& a, const RowRef& R, u
     }
   }
   uint32_t* cid = hist + NBINS;
-  finish_regs<PER, true>(a, R, vid, zv, zq, ok, filter, 0u, zcx, zpx, hist, cid,
+  finish_regs<PER, true, GS>(a, R, vid, zv, zq, ok, filter, 0u, zcx, zpx, hist, cid,
                    reinterpret_cast<float*>(cid + kKeptCap),
                    reinterpret_cast<float*>(cid + 2 * kKeptCap), kKeptCap, sm, out);
 }
 
+template <bool GS>
 __global__ __launch_bounds__(THREADS) void row_kernel(const RowArgs a, const int P, const int capE) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   __shared__ Small sm;
@@ -856,6 +903,7 @@ __global__ __launch_bounds__(THREADS) void row_kernel(const RowArgs a, const int
     if (tid == 0) {
       a.y[R.widx] = -1;
       a.k[R.widx] = 1;
+      if (GS) a.g[R.widx] = -1;
       if (a.px) a.px[R.widx] = 0.f;
       if (a.qx) a.qx[R.widx] = 0.f;
       if (a.mode == kRowRing && R.s == 0) a.accept_len[R.b] = 0;   // finished sequence
@@ -873,8 +921,8 @@ __global__ __launch_bounds__(THREADS) void row_kernel(const RowArgs a, const int
   bool done = false;
   if (n <= kDirectMaxN) {
     // ---- the whole row in registers ------------------------------------------------
-    if (n <= kDirectMaxN / 2) direct_path<PER_DIRECT / 2>(a, R, smem, filter, zcx, zpx, sm, out);
-    else direct_path<PER_DIRECT>(a, R, smem, filter, zcx, zpx, sm, out);
+    if (n <= kDirectMaxN / 2) direct_path<PER_DIRECT / 2, GS>(a, R, smem, filter, zcx, zpx, sm, out);
+    else direct_path<PER_DIRECT, GS>(a, R, smem, filter, zcx, zpx, sm, out);
     done = true;
   } else if (filter && a.cand && P > 0) {
     // ---- candidates emitted by the slice kernel ----------------------------------
@@ -920,12 +968,12 @@ __global__ __launch_bounds__(THREADS) void row_kernel(const RowArgs a, const int
 #pragma unroll
       for (int e = 0; e < PER_LIST; ++e) zq[e] = 0.f;
       const int ccap = min(kKeptCap, static_cast<int>(static_cast<size_t>((n + 7) & ~7) * 2 / 12));
-      done = finish_regs<PER_LIST, false>(a, R, vid, zv, zq, ok, true, cut_max, zcx, zpx, hist,
+      done = finish_regs<PER_LIST, false, GS>(a, R, vid, zv, zq, ok, true, cut_max, zcx, zpx, hist,
                                    reinterpret_cast<uint32_t*>(smem), reinterpret_cast<float*>(smem) + ccap,
                                    reinterpret_cast<float*>(smem) + 2 * ccap, ccap, sm, out);
     }
   }
-  if (!done) full_path(a, R, smem, zcx, zpx, sm, out);
+  if (!done) full_path<GS>(a, R, smem, zcx, zpx, sm, out);
   if (a.mode == kRowSelectOnly) return;
 
   // ---- winner of the race (lexicographic (score, id) minimum) -------------------
@@ -952,12 +1000,34 @@ __global__ __launch_bounds__(THREADS) void row_kernel(const RowArgs a, const int
       k_out = 0;
     }
   }
+  // ---- Gumbel-sharing draft of the row: the same reduction over (score, id) ---------
+  int g_out = -1;
+  if (GS) {
+    float gb = out.gbest;
+    int gi = out.gbest_id;
+    wave_min_score_id(gb, gi);
+    __syncthreads();               // the exchange arrays may still be read by the race above
+    if (lane == 0) {
+      sm.s_score[wave] = gb;
+      sm.s_id[wave] = gi;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int w = 0; w < NW; ++w) {
+      if (sm.s_score[w] < gb || (sm.s_score[w] == gb && sm.s_id[w] < gi)) {
+        gb = sm.s_score[w];
+        gi = sm.s_id[w];
+      }
+    }
+    g_out = gi != 0x7FFFFFFF ? gi : R.x;   // empty support cannot happen (the maximum is kept)
+  }
   if (a.mode != kRowRing) {
     if (tid == 0) {
       a.y[R.widx] = y_out;
       a.k[R.widx] = static_cast<uint8_t>(k_out);
       if (a.px) a.px[R.widx] = out.px;
       if (a.qx) a.qx[R.widx] = out.qx;
+      if (GS) a.g[R.widx] = g_out;
     }
     return;
   }
@@ -973,6 +1043,7 @@ __global__ __launch_bounds__(THREADS) void row_kernel(const RowArgs a, const int
   if (tid == 0) {
     __hip_atomic_store(&a.y[R.widx], y_out, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     __hip_atomic_store(&a.k[R.widx], static_cast<uint8_t>(k_out), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (GS) __hip_atomic_store(&a.g[R.widx], g_out, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     if (a.px) a.px[R.widx] = out.px;
     if (a.qx) a.qx[R.widx] = out.qx;
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
@@ -982,9 +1053,11 @@ __global__ __launch_bounds__(THREADS) void row_kernel(const RowArgs a, const int
   __syncthreads();
   if (!sm.last) return;
   __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
-  int yy = -1;
+  int yy = -1, gg = -1;
   if (tid < live) {
     yy = __hip_atomic_load(&a.y[static_cast<size_t>(b) * a.L + tid], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (GS)
+      gg = __hip_atomic_load(&a.g[static_cast<size_t>(b) * a.L + tid], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     const uint8_t kk = __hip_atomic_load(&a.k[static_cast<size_t>(b) * a.L + tid], __ATOMIC_RELAXED,
                                          __HIP_MEMORY_SCOPE_AGENT);
     if (kk == 0) atomicMin(&sm.first_rej, tid);
@@ -995,7 +1068,9 @@ __global__ __launch_bounds__(THREADS) void row_kernel(const RowArgs a, const int
   if (tid < live) {
     const size_t sidx = static_cast<size_t>(b) * a.L + (p0 + tid) % a.L;
     if (tid >= acc) {
-      a.X[sidx] = yy;
+      // survivors: the MRS output is the coupled redraft (pi_MC); under pi_GS the redraft
+      // is the shared-noise Gumbel draw from the new distribution
+      a.X[sidx] = GS ? gg : yy;
       a.age_w[sidx] += 1;
     } else {
       const int np = p0 + a.L + tid;
@@ -1049,13 +1124,18 @@ hipError_t launch_row(const RowArgs& a_in, hipStream_t s) {
   const size_t lds = lds_bytes_for(a.n);
   static size_t configured = 0;          // grows monotonically; benign if raced (idempotent call)
   if (lds > configured) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(row_kernel),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize,
-                                       static_cast<int>(lds));
-    if (e != hipSuccess) return e;
+    for (const void* f : {reinterpret_cast<const void*>(row_kernel<false>),
+                          reinterpret_cast<const void*>(row_kernel<true>)}) {
+      hipError_t e = hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                         static_cast<int>(lds));
+      if (e != hipSuccess) return e;
+    }
     configured = lds;
   }
-  hipLaunchKernelGGL(row_kernel, dim3(a.rows), dim3(THREADS), lds, s, a, P, capE);
+  if (a.gumbel && a.g && a.mode != kRowSelectOnly)
+    hipLaunchKernelGGL(row_kernel<true>, dim3(a.rows), dim3(THREADS), lds, s, a, P, capE);
+  else
+    hipLaunchKernelGGL(row_kernel<false>, dim3(a.rows), dim3(THREADS), lds, s, a, P, capE);
   return hipGetLastError();
 }
 

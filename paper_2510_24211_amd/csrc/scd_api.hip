@@ -32,6 +32,7 @@ bool valid_config(const scd_config* c) {
   if (!(c->temperature > 0.f) || !std::isfinite(c->temperature)) return false;
   if (!std::isfinite(c->cfg_lambda)) return false;
   if (c->reserved != 0) return false;
+  if (c->coupling < 0) return false;
   return true;
 }
 
@@ -55,6 +56,7 @@ Layout make_layout(const scd_config& c) {
   sz[SCD_F_FLAGS] = 16;
   sz[SCD_F_VERIFIED] = 4 * B;
   sz[SCD_F_TICKET] = 4 * B;
+  sz[SCD_F_G] = 4 * B * L;
   Layout lay;
   size_t o = 0;
   for (int f = 0; f < SCD_F_COUNT; ++f) {
@@ -130,6 +132,8 @@ int run_tail(scd_ctx* c, void* st) {
     ra.B = c->cfg.B; ra.L = c->cfg.L; ra.N = c->cfg.N; ra.n = c->n; ra.top_k = c->cfg.top_k;
     ra.v_lo = c->cfg.v_lo; ra.seed = c->cfg.seed;
     ra.cand_base = static_cast<char*>(c->ws) + small_need(c->cfg);
+    ra.gumbel = c->cfg.coupling == SCD_COUPLING_GS;
+    ra.g = field<int32_t>(c, st, SCD_F_G);
     return hip_rc(scd::launch_row(ra, c->stream));
   }
   // rows too long for the LDS-resident kernel: select -> MRS -> commit
@@ -194,7 +198,10 @@ size_t scd_state_bytes(const scd_config* cfg) {
 int scd_create(scd_ctx** out, const scd_config* cfg, void* d_workspace, size_t workspace_bytes,
                void* hip_stream) {
   if (!out || !valid_config(cfg)) return SCD_EINVAL;
-  if (cfg->coupling != 0) return SCD_EUNSUPPORTED;
+  if (cfg->coupling != SCD_COUPLING_MC && cfg->coupling != SCD_COUPLING_GS) return SCD_EUNSUPPORTED;
+  // the Gumbel draw lives in the fused row kernel only
+  if (cfg->coupling == SCD_COUPLING_GS && cfg->v_hi - cfg->v_lo > scd::kRowKernelMaxN)
+    return SCD_EUNSUPPORTED;
   if (!d_workspace || !aligned(d_workspace, kAlign) || workspace_bytes < workspace_need(*cfg))
     return SCD_EWORKSPACE;
   scd_ctx* c = new (std::nothrow) scd_ctx;

@@ -94,6 +94,10 @@ struct RowArgs {
   int32_t* verified;     // [B]
   int32_t* accept_len;   // [B]
   int32_t* out;          // [B, N]
+  // Gumbel-sharing coupling: with gumbel != 0 and g non-null every row also draws
+  // g = argmax_v(log p_v + G_v(position)) and the survivors' next drafts are g, not y
+  int gumbel;
+  int32_t* g;            // [B, L] window order
   int rows;              // select-only: rows; else B*L
   int B, L, N, n, top_k, v_lo;
   uint64_t seed;

@@ -28,17 +28,19 @@ def bf16_tensor(bits_np, device):
 
 
 class LockStep:
-    def __init__(self, w: wl.Workload, device="cuda:0", check_logits=True):
+    def __init__(self, w: wl.Workload, device="cuda:0", check_logits=True, coupling="mc"):
         self.w = w
         self.device = device
         self.check_logits = check_logits
+        self.coupling = coupling
         self.cfg_c = B.config_from_workload(w)
+        self.cfg_c.coupling = B.COUPLING_GS if coupling == "gs" else B.COUPLING_MC
         self.gpu = B.Scd(self.cfg_c, device)
         self.state = self.gpu.alloc_state()
         self.gpu.reset(self.state)
         self.ocfg = oscd.ScdConfig(B=w.B, L=w.L, N=w.N, V=w.V, v_lo=w.v_lo, v_hi=w.v_hi,
                                    top_k=w.top_k, temperature=w.temperature,
-                                   cfg_lambda=w.cfg_lambda, seed=w.seed)
+                                   cfg_lambda=w.cfg_lambda, seed=w.seed, coupling=coupling)
         self.oracle = oscd.ScdOracle(self.ocfg)
         self.n = w.n_allowed
         if w.d > 0:
@@ -54,9 +56,9 @@ class LockStep:
             ("pos", B.F_POS), ("iter", B.F_ITER), ("X", B.F_X), ("age", B.F_AGE), ("out", B.F_OUT),
             ("acc", B.F_ACCEPT), ("y", B.F_Y), ("k", B.F_K), ("px", B.F_PX), ("qx", B.F_QX),
             ("thr", B.F_THR), ("lse", B.F_LSE), ("nkept", B.F_NKEPT), ("z", B.F_Z),
-            ("verified", B.F_VERIFIED)]}
-        self.stats = dict(steps=0, draws=0, flag_accept=0, flag_resid=0, flag_topk=0,
-                          adopt_accept=0, adopt_resid=0, adopt_topk=0,
+            ("verified", B.F_VERIFIED), ("g", B.F_G)]}
+        self.stats = dict(steps=0, draws=0, flag_accept=0, flag_resid=0, flag_topk=0, flag_gs=0,
+                          adopt_accept=0, adopt_resid=0, adopt_topk=0, adopt_gs=0,
                           max_logit_abs=0.0, max_logit_rel=0.0, max_lse_abs=0.0, max_prob_rel=0.0)
         lam = w.cfg_lambda
         self.logit_tol = 1e-5 * (1 + 2 * lam)
@@ -108,7 +110,7 @@ class LockStep:
 
         # ---- download what the step produced --------------------------------
         g = {k: v[k].cpu().numpy() for k in ("pos", "iter", "X", "age", "acc", "y", "k", "px",
-                                             "qx", "thr", "lse", "nkept", "verified")}
+                                             "qx", "thr", "lse", "nkept", "verified", "g")}
         g["thr"] = g["thr"].reshape(2, Bn, L)
         g["lse"] = g["lse"].reshape(2, Bn, L)
         g["nkept"] = g["nkept"].reshape(2, Bn, L)
@@ -166,7 +168,8 @@ class LockStep:
 
         # ---- one MRS per window position -----------------------------------
         res = o.sample(plan)
-        acc_ov, res_ov = {}, {}
+        acc_ov, res_ov, gs_ov = {}, {}, {}
+        gg = g["g"].reshape(Bn, L)
         gk = g["k"].reshape(Bn, L)
         gy = g["y"].reshape(Bn, L)
         gpx = g["px"].reshape(Bn, L)
@@ -192,9 +195,15 @@ class LockStep:
                 elif r["k"] == 0 and int(gy[b, s]) != r["y"]:
                     assert r["flag_resid"], f"residual token differs on an unflagged draw b={b} s={s}"
                     res_ov[key] = int(gy[b, s])
-        if acc_ov or res_ov:
+                if self.coupling == "gs":
+                    st["flag_gs"] += r["flag_gs"]
+                    if int(gg[b, s]) != r["g"]:
+                        assert r["flag_gs"], f"Gumbel draw differs on an unflagged draw b={b} s={s}"
+                        gs_ov[key] = int(gg[b, s])
+        if acc_ov or res_ov or gs_ov:
             st["adopt_accept"] += len(acc_ov)
-            res = o.sample(plan, acc_ov, res_ov)
+            st["adopt_gs"] += len(gs_ov)
+            res = o.sample(plan, acc_ov, res_ov, gs_ov)
             for (b, j), kk in acc_ov.items():     # a forced rejection resamples: token may be flagged too
                 s = j - i_b[b]
                 if kk == 0 and res[b][s]["y"] != int(gy[b, s]):
@@ -202,13 +211,17 @@ class LockStep:
                     res_ov[(b, j)] = int(gy[b, s])
             st["adopt_resid"] += len(res_ov)
             if res_ov:
-                res = o.sample(plan, acc_ov, res_ov)
+                res = o.sample(plan, acc_ov, res_ov, gs_ov)
         for b in range(Bn):
             for s in range(L):
                 if s < lives[b]:
                     assert int(gk[b, s]) == res[b][s]["k"] and int(gy[b, s]) == res[b][s]["y"]
+                    if self.coupling == "gs":
+                        assert int(gg[b, s]) == res[b][s]["g"]
                 else:
                     assert int(gk[b, s]) == 1 and int(gy[b, s]) == -1
+                    if self.coupling == "gs":
+                        assert int(gg[b, s]) == -1
 
         # ---- commit --------------------------------------------------------
         acc = o.commit(plan, res)

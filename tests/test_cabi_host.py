@@ -59,8 +59,10 @@ def test_create_rejects_bad_arguments_without_touching_the_device():
         == B.SCD_EWORKSPACE                                   # misaligned
     assert lib.scd_create(ctypes.byref(ctx), ctypes.byref(cfg), fake, need - 1, None) == B.SCD_EWORKSPACE
     assert lib.scd_create(None, ctypes.byref(cfg), fake, need, None) == B.SCD_EINVAL
-    bad = B.make_config(B=1, L=8, N=64, V=1024, coupling=1)
+    bad = B.make_config(B=1, L=8, N=64, V=1024, coupling=2)           # no such coupling
     assert lib.scd_create(ctypes.byref(ctx), ctypes.byref(bad), fake, need, None) == B.SCD_EUNSUPPORTED
+    big = B.make_config(B=1, L=8, N=64, V=70000, coupling=B.COUPLING_GS)   # GS: rows <= 65536 ids
+    assert lib.scd_create(ctypes.byref(ctx), ctypes.byref(big), fake, 1 << 40, None) == B.SCD_EUNSUPPORTED
     assert lib.scd_create(ctypes.byref(ctx), ctypes.byref(cfg), fake, need, None) == B.SCD_OK
     # null pointers are refused before any launch
     assert lib.scd_lm_head(ctx, None, None, None) == B.SCD_EINVAL
@@ -75,7 +77,7 @@ def test_create_rejects_bad_arguments_without_touching_the_device():
     total = B.state_bytes(cfg)
     base = 0x100000
     spans = []
-    for f in range(17):
+    for f in range(18):
         p, nb = ctypes.c_void_p(), ctypes.c_size_t()
         assert lib.scd_state_field(ctx, ctypes.c_void_p(base), f, ctypes.byref(p), ctypes.byref(nb)) == 0
         assert p.value % 256 == 0 and nb.value > 0
@@ -83,7 +85,7 @@ def test_create_rejects_bad_arguments_without_touching_the_device():
     spans.sort()
     assert spans[-1][1] <= total
     assert all(a[1] <= b[0] for a, b in zip(spans, spans[1:]))
-    assert lib.scd_state_field(ctx, ctypes.c_void_p(base), 17, ctypes.byref(p), ctypes.byref(nb)) == B.SCD_EINVAL
+    assert lib.scd_state_field(ctx, ctypes.c_void_p(base), 18, ctypes.byref(p), ctypes.byref(nb)) == B.SCD_EINVAL
     assert lib.scd_destroy(ctx) == B.SCD_OK
     assert lib.scd_destroy(None) == B.SCD_EINVAL
     assert B.strerror(B.SCD_EWORKSPACE).startswith("workspace")

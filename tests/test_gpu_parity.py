@@ -241,6 +241,48 @@ def test_lockstep_C4_prefix():
     _lockstep(wl.WORKLOADS["C4"], max_steps=3)
 
 
+# ----------------------------------------- Gumbel-sharing coupling (pi_GS)
+@pytest.mark.parametrize("kw", [
+    dict(N=64, L=8, seed=0),                        # the toy workload itself
+    dict(N=33, L=1, seed=22),                       # plain autoregressive sampling
+    dict(N=50, L=16, seed=23, top_k=64),
+    dict(N=70, L=8, seed=24, B=3, V=1000),          # batch, ragged n
+    dict(N=40, L=8, seed=25, V=12000, top_k=300, age_cap=4),   # 16 logits per thread
+    dict(N=20, L=4, seed=26, V=65536, top_k=2000, age_cap=4),  # slice kernel + candidate path
+    dict(N=16, L=4, seed=27, V=20000, age_cap=4),              # no top-k on a long row: in-place path
+])
+def test_lockstep_gs_toy_variants(kw):
+    ls, st = _lockstep(wl.scaled(wl.WORKLOADS["C0"], name="toy-gs", **kw), coupling="gs")
+    assert st["adopt_gs"] <= max(2, 1e-3 * st["draws"])
+
+
+def test_lockstep_gs_scaled_cfg_masked_batched():
+    ls, st = _lockstep(wl.scaled(wl.WORKLOADS["C3"], name="C3s-gs", B=4, N=80, V=4096, d=256, v_lo=4,
+                                 v_hi=1028, top_k=250), coupling="gs")
+    assert st["adopt_gs"] <= max(2, 1e-3 * st["draws"])
+
+
+def test_lockstep_gs_C1_full_and_C2_prefix():
+    _lockstep(wl.WORKLOADS["C1"], check_logits=False, coupling="gs")
+    _lockstep(wl.WORKLOADS["C2"], max_steps=25, coupling="gs")
+
+
+def test_gs_redraft_is_stable_where_mc_is_not_required_to_be():
+    # p == q bit for bit (ages past the cap): the Gumbel draft of a position repeats exactly,
+    # iteration after iteration, because its noise does not depend on the iteration.
+    from lockstep import LockStep
+    w = wl.scaled(wl.WORKLOADS["C0"], name="toy-gs-const", N=24, L=8, seed=31, age_cap=0)
+    ls = LockStep(w, DEV, coupling="gs")
+    ls.step()                                   # every window position evaluated once
+    X1 = ls.v["X"].cpu().numpy().copy()
+    pos1 = int(ls.v["pos"].cpu().numpy()[0])
+    ls.step()
+    X2 = ls.v["X"].cpu().numpy()
+    pos2 = int(ls.v["pos"].cpu().numpy()[0])
+    for j in range(pos2, min(pos1 + w.L, w.N)):  # positions that were in both windows and survive
+        assert X1[j % w.L] == X2[j % w.L]
+
+
 # --------------------------------------------------------------- edge cases
 def test_determinism_and_finished_sequences_untouched():
     w = wl.scaled(wl.WORKLOADS["C1"], name="det", N=64, V=1024, d=128, top_k=100, B=2)
