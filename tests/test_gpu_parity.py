@@ -37,6 +37,13 @@ def _require_gpu_and_library():
     (5, 40, 128, 640, 0, 640, 1.5, 1.0),        # L not a multiple of 32, odd B
     (1, 1, 64, 256, 0, 256, 0.0, 1.0),          # L = 1
     (16, 32, 256, 512, 0, 512, 3.0, 1.0),       # several row-block tiles share a W slab
+    # split-k kernel with XCD-affine row groups of G = 128 KB / row bytes rows, ragged against 8 G,
+    # first allowed row not on a block boundary:
+    (1, 32, 2048, 4096, 3, 4000, 3.0, 1.0),     # G = 32, 4 k parts
+    (1, 32, 1024, 3000, 0, 3000, 0.0, 1.0),     # G = 64
+    (1, 32, 8192, 1500, 5, 1400, 3.0, 1.0),     # G = 8, 8 k parts
+    (2, 32, 4096, 2500, 7, 2407, 3.0, 1.0),     # G = 16, two row blocks per workgroup
+    (4, 32, 4096, 1000, 0, 1000, 3.0, 1.0),     # G = 16 available but many row blocks: wide kernel
 ])
 def test_lm_head_against_oracle(Bn, L, d, V, v_lo, v_hi, lam, tau):
     g = np.random.default_rng(hash((Bn, L, d, V)) % 2 ** 32)
