@@ -174,7 +174,10 @@ __global__ __launch_bounds__((Cfg<RBW, C, NWV>::THREADS)) void lm_head_kernel(
   const int KT = (d + BK - 1) / BK;
   const int ntiles = KT;
   const int ntiles_pad = (ntiles + D - 1) / D * D;
-  const int rot = (vt * 5) % ntiles_pad;
+  // Row tiles that share a slab of W, and column tiles that share the same h rows, read the same
+  // bytes; with several row tiles (MT > 1: the h rows no longer fit one L2 beside the W stream)
+  // all workgroups of an XCD therefore start at the same k, so that they meet in L2 (C3: 86 -> 82 us).
+  const int rot = (MT > 1 ? xcd * 5 : vt * 5) % ntiles_pad;
   // logical tile t -> k-tile index; `valid` is false for the padding tiles of the rotation
   // and for prefetches past the end.  Loads are NEVER predicated (a predicated load is a
   // branch, and branches keep the scheduler from batching the loads): an invalid tile reads
