@@ -28,6 +28,8 @@ STREAM_INIT = 0    # initial draft token of a never-evaluated position
 STREAM_ACCEPT = 1  # the uniform of the accept test
 STREAM_RESID = 2   # one uniform per vocab id for the residual race
 STREAM_GUMBEL = 3  # one uniform per vocab id for the shared Gumbel noise of a position
+STREAM_ALPHA = 4   # the Bernoulli(alpha) switch of the alpha-coupling
+STREAM_INDEP = 5   # one uniform per vocab id for an independent draw from p
 
 
 def philox4x32_10(c0, c1, c2, c3, k0, k1):

@@ -41,6 +41,13 @@ with G_j a function of the position only.  Further readings for it:
   * the vectorised form evaluates the MRS call of every window position (the
     calls right of the first rejection are discarded) and the Gumbel draw of
     every window position (the draws left of it are discarded).
+
+alpha-coupling (Sec. 5.3 "Coupling Strength", appendix Alg. "alpha-Coupling
+Implementation"): pi^alpha = alpha * pi_cpl + (1 - alpha) * pi_ind.  Per redraft one
+uniform u; if u <= alpha the coupled redraft above is taken, otherwise an
+independent draw X ~ p (here: a Gumbel-max / exponential-race draw with noise
+keyed by position AND iteration, i.e. fresh every time).  alpha = 1 is SCD,
+alpha = 0 is vanilla SJD.  Only the redraft changes; verification does not.
 """
 from dataclasses import dataclass, field
 import numpy as np
@@ -64,11 +71,13 @@ class ScdConfig:
     cfg_lambda: float = 0.0  # 0 => no CFG
     seed: int = 0
     coupling: str = "mc"     # "mc": maximal coupling (MRS redraft); "gs": Gumbel sharing
+    alpha: float = 1.0       # coupling strength: probability of the coupled redraft
 
     def __post_init__(self):
         if self.v_hi < 0:
             self.v_hi = self.V
         assert self.coupling in ("mc", "gs")
+        assert 0.0 <= self.alpha <= 1.0
 
     @property
     def n_allowed(self):
@@ -197,15 +206,28 @@ class ScdOracle:
                         and resid_override[key] != r["y"]:
                     assert r["flag_resid"], "residual override on an unflagged draw"
                     r["y"] = int(resid_override[key])
-                if cfg.coupling == "gs":
+                # what a surviving position drafts next
+                indep = False
+                if cfg.alpha < 1.0:
+                    # u <= alpha, decided in fp32 like every other threshold test of the path
+                    ua = philox.uniform_scalar(cfg.seed, b, j, t, philox.STREAM_ALPHA)
+                    indep = not (np.float32(ua) <= np.float32(cfg.alpha))
+                r["indep"] = indep
+                Ug = None
+                if indep:          # fresh noise: keyed by the iteration too
+                    Ug = philox.uniform_per_vocab(cfg.seed, b, j, t, philox.STREAM_INDEP,
+                                                  cfg.n_allowed)
+                elif cfg.coupling == "gs":   # shared noise: keyed by the position only
                     Ug = philox.uniform_per_vocab(cfg.seed, b, j, 0, philox.STREAM_GUMBEL,
                                                   cfg.n_allowed)
+                if Ug is not None:
                     g, _ = gs_mod.draw(p, Ug)
                     r["flag_gs"] = gs_mod.flag(p, Ug, g, self.tol)
                     if gs_override and key in gs_override and gs_override[key] != g:
                         assert r["flag_gs"], "Gumbel override on an unflagged draw"
                         g = int(gs_override[key])
                     r["g"] = g
+                r["next"] = r["g"] if Ug is not None else r["y"]
                 rows.append(r)
             res.append(rows)
         return res
@@ -229,7 +251,7 @@ class ScdOracle:
                 self.out[b, i + s] = cfg.v_lo + res[b][s]["y"]
             for s in range(a, Lw):                    # survivors: coupled redraft
                 j = i + s
-                self.X[b, j] = res[b][s]["g" if cfg.coupling == "gs" else "y"]
+                self.X[b, j] = res[b][s]["next"]
                 self.q[b][j] = plan[b][s]["p"]
                 self.age[b, j] += 1
             for s in range(a):                        # retired positions
@@ -291,7 +313,11 @@ def decode_sequential(cfg: ScdConfig, model, tol=1e-5):
             # been used on them yet (positions right of the last rejection).
             for j in range(i, i + Lw):
                 if j in p_new:
-                    if cfg.coupling == "gs":
+                    ua = philox.uniform_scalar(cfg.seed, b, j, t_new[j], philox.STREAM_ALPHA)
+                    if cfg.alpha < 1.0 and not (np.float32(ua) <= np.float32(cfg.alpha)):
+                        Ui = philox.uniform_per_vocab(cfg.seed, b, j, t_new[j], philox.STREAM_INDEP, n)
+                        X[j] = gs_mod.draw(p_new[j], Ui)[0]
+                    elif cfg.coupling == "gs":
                         Ug = philox.uniform_per_vocab(cfg.seed, b, j, 0, philox.STREAM_GUMBEL, n)
                         X[j] = gs_mod.draw(p_new[j], Ug)[0]
                     else:

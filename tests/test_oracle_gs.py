@@ -159,3 +159,63 @@ def test_noise_depends_on_the_position_only():
                 rhs += (1 - tv) / (1 + tv)
         o.commit(plan, res)
     assert lhs >= rhs - 3.0 * np.sqrt(max(rhs, 1.0))
+
+
+# ------------------------------------------------------------------ alpha-coupling
+def test_alpha_one_is_scd_and_forms_agree_for_every_alpha():
+    for coupling in ("mc", "gs"):
+        w, cfg, model = _toy(N=40, L=8, seed=41)
+        cfg.coupling = coupling
+        base = scd.decode(cfg, model).out.copy()
+        cfg.alpha = 1.0
+        assert np.array_equal(scd.decode(cfg, model).out, base)
+        for alpha in (0.0, 0.3, 0.8):
+            cfg.alpha = alpha
+            o = scd.decode(cfg, model)
+            out, nfe, hist = scd.decode_sequential(cfg, model)
+            assert np.array_equal(o.out, out) and o.t == nfe and o.accept_hist == hist
+        cfg.alpha = 0.0
+        assert not np.array_equal(scd.decode(cfg, model).out, base)
+
+
+def test_alpha_mixture_collision_probability():
+    # Sec. 5.3: pi^alpha = alpha pi_cpl + (1 - alpha) pi_ind, so the probability that a redraft
+    # equals the previous draft is alpha * C_cpl + (1 - alpha) * sum_v p_v q_v.  Measured over a
+    # decode on positions whose previous draft came from q (survivors of an earlier redraft).
+    for alpha in (0.0, 0.5):
+        lhs = rhs = 0.0
+        var = 0.0
+        for seed in range(40, 52):
+            w, cfg, model = _toy(N=48, L=8, seed=seed, V=24)
+            cfg.alpha = alpha
+            o = scd.ScdOracle(cfg)
+            while not o.done():
+                i, Lw = o.window(0)
+                plan = o.evaluate([model(0, i, Lw, None, o.t[0], o.age[0, i:i + Lw].copy())])
+                res = o.sample(plan)
+                for s in range(Lw):
+                    if i + s in o.q[0]:
+                        p, q = plan[0][s]["p"], o.q[0][i + s]
+                        c_mc = 1 - 0.5 * np.abs(p - q).sum()          # maximal coupling: 1 - TV
+                        pr = alpha * c_mc + (1 - alpha) * float((p * q).sum())
+                        lhs += float(res[0][s]["next"] == o.X[0, i + s])
+                        rhs += pr
+                        var += pr * (1 - pr)
+                o.commit(plan, res)
+        assert abs(lhs - rhs) <= 4.0 * np.sqrt(var) + 1.0, (alpha, lhs, rhs)
+
+
+def test_end_to_end_lossless_for_alpha_below_one():
+    V, N = 3, 3
+    model = ToyContextModel(V, N, seed=7)
+    want = model.ar_joint(0)
+    for alpha, coupling in ((0.0, "mc"), (0.5, "gs")):
+        counts = {k: 0 for k in want}
+        runs = 10000
+        for r in range(runs):
+            cfg = ScdConfig(B=1, L=3, N=N, V=V, seed=3100000 + r, coupling=coupling, alpha=alpha)
+            counts[tuple(int(x) for x in scd.decode(cfg, model).out[0])] += 1
+        keys = list(want)
+        obs = np.array([counts[k] for k in keys], dtype=np.float64)
+        exp = np.array([want[k] for k in keys]) * runs
+        assert stats.chisquare(obs, exp).pvalue > 1e-4, (alpha, coupling)
