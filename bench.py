@@ -41,6 +41,9 @@ def parse():
                     help="C1 | C2 | C2-fullV | C3 | C4 (see paper_2510_24211_amd/workload.py)")
     ap.add_argument("--coupling", default="mc", choices=["mc", "gs"],
                     help="mc: maximal coupling (the paper's pi_MC, default); gs: Gumbel sharing (pi_GS)")
+    ap.add_argument("--sjd-mix", type=float, default=0.0,
+                    help="1 - alpha of the alpha-coupling: probability that a redraft is an independent "
+                         "draw (0 = SCD, default; 1 = vanilla SJD)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=15.0)
     ap.add_argument("--quick", action="store_true",
@@ -92,7 +95,7 @@ class HipEvents:
             self.hip.hipEventDestroy(e)
 
 
-def cpu_baseline(w, seconds, coupling="mc"):
+def cpu_baseline(w, seconds, coupling="mc", sjd_mix=0.0):
     """The oracle as it stands, on the host cores, for about `seconds` (whole decodes are
     repeated until the time is up; the last one may be cut short)."""
     import numpy as np
@@ -110,7 +113,7 @@ def cpu_baseline(w, seconds, coupling="mc"):
     tab = wl.HiddenTable(w)
     cfg = oscd.ScdConfig(B=w.B, L=w.L, N=w.N, V=w.V, v_lo=w.v_lo, v_hi=w.v_hi, top_k=w.top_k,
                          temperature=w.temperature, cfg_lambda=w.cfg_lambda, seed=w.seed,
-                         coupling=coupling)
+                         coupling=coupling, alpha=float(np.float32(1.0) - np.float32(sjd_mix)))
     o = oscd.ScdOracle(cfg)
     tab.window(list(o.i), [[0] * w.L for _ in range(w.B)])      # warm the generator caches
     t_in = 0.0
@@ -179,7 +182,7 @@ def main():
                                                          "ms_per_step", "config", "roofline")}
     inputs.clear()
     if not a.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(w, a.cpu_seconds, a.coupling)
+        out["cpu_baseline"] = cpu_baseline(w, a.cpu_seconds, a.coupling, a.sjd_mix)
     print(json.dumps(out))
 
 
@@ -206,6 +209,7 @@ def measure(a, name, inputs):
     W, table = inputs["W"], inputs["table"]
     cfg = B.config_from_workload(w)
     cfg.coupling = B.COUPLING_GS if a.coupling == "gs" else B.COUPLING_MC
+    cfg.sjd_mix = a.sjd_mix
     s = B.Scd(cfg, dev)
     st = s.alloc_state()
     h = torch.empty((w.B, w.C, w.L, w.d), dtype=torch.bfloat16, device=dev)
@@ -354,7 +358,7 @@ def measure(a, name, inputs):
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": f"{w.name}: B={w.B} CFG={'on' if w.C == 2 else 'off'} L={w.L} "
                                f"N={w.N} V={w.V} allowed={n} d={w.d} top_k={w.top_k} "
-                               f"lambda={w.cfg_lambda} seed={w.seed} coupling={a.coupling} "
+                               f"lambda={w.cfg_lambda} seed={w.seed} coupling={a.coupling} sjd_mix={a.sjd_mix} "
                                f"(synthetic drift model)",
                    "decode_iterations": None if a.quick else int(nfe),
                    "tokens_per_iteration": None if a.quick else w.B * w.N / nfe,

@@ -25,6 +25,10 @@
  *        g = argmax_v (log p(v) + G_j(v)),  G_j(v) = -ln(-ln U_j(v)),
  * with noise that depends on the position j (and the id v) only, not on the iteration,
  * decided as the equivalent exponential race argmin_v -ln(U_j(v)) / p(v) in fp32.
+ * With sjd_mix > 0 (alpha-coupling, Sec. 5.3 and appendix Alg. "alpha-Coupling
+ * Implementation", alpha = 1 - sjd_mix): per redraft one uniform u (stream 4); if
+ * u <= alpha (fp32, alpha = fl(1 - sjd_mix)) the coupled redraft above is taken, otherwise an
+ * independent draw from p: the same race with noise keyed by position AND iteration (stream 5).
  *
  * Conventions
  *   - Every pointer named d_* is a DEVICE pointer owned by the caller.  The
@@ -44,7 +48,7 @@
  *     counter = (vocab offset >> 2 or 0, position, iteration, b << 8 | stream),
  *     lane = vocab offset & 3 (lane 0 for scalar draws); streams 0 = initial
  *     draft, 1 = accept uniform, 2 = residual race, 3 = Gumbel noise (iteration
- *     word 0).
+ *     word 0), 4 = alpha-coupling switch, 5 = independent redraft.
  *     u = ((bits >> 9) + 0.5) * 2^-23.
  */
 #ifndef SCD_H
@@ -70,7 +74,9 @@ typedef struct scd_config {
   float temperature;   /* tau > 0                                                   */
   float cfg_lambda;    /* 0 => no guidance (C = 1); else C = 2, z = (1+l)c - l u    */
   int32_t coupling;    /* scd_coupling: 0 = maximal coupling (MRS), 1 = Gumbel sharing */
-  int32_t reserved;    /* must be 0                                                 */
+  float sjd_mix;       /* 1 - alpha of the alpha-coupling (Sec. 5.3): probability that a
+                          redraft is an independent draw from p instead of the coupled one;
+                          0 = SCD (default), 1 = vanilla SJD; must be in [0, 1]          */
   uint64_t seed;
 } scd_config;
 
@@ -108,8 +114,9 @@ typedef enum scd_field {
   SCD_F_FLAGS = 14,   /* int32 [4]       [0] numeric-fault bits                        */
   SCD_F_VERIFIED = 15,/* int32 [B]       window positions verified so far (sum of Lw)  */
   SCD_F_TICKET = 16,  /* int32 [B]       internal arrival counters, zero between steps */
-  SCD_F_G = 17,       /* int32 [B, L]    last step's Gumbel-sharing draws, window order
-                                         (written under SCD_COUPLING_GS only)          */
+  SCD_F_G = 17,       /* int32 [B, L]    last step's Gumbel-sharing / independent redraft draws,
+                                         window order; -1 where the row drew none (written
+                                         under SCD_COUPLING_GS or sjd_mix > 0 only)      */
   SCD_F_COUNT = 18
 } scd_field;
 

@@ -34,7 +34,7 @@ class ScdConfig(ctypes.Structure):
                 ("V", ctypes.c_int32), ("d", ctypes.c_int32), ("v_lo", ctypes.c_int32),
                 ("v_hi", ctypes.c_int32), ("top_k", ctypes.c_int32),
                 ("temperature", ctypes.c_float), ("cfg_lambda", ctypes.c_float),
-                ("coupling", ctypes.c_int32), ("reserved", ctypes.c_int32),
+                ("coupling", ctypes.c_int32), ("sjd_mix", ctypes.c_float),
                 ("seed", ctypes.c_uint64)]
 
 
@@ -94,9 +94,9 @@ def strerror(code):
 
 
 def make_config(B, L, N, V, d=0, v_lo=0, v_hi=-1, top_k=0, temperature=1.0, cfg_lambda=0.0,
-                seed=0, coupling=0):
+                seed=0, coupling=0, sjd_mix=0.0):
     return ScdConfig(B, L, N, V, d, v_lo, V if v_hi < 0 else v_hi, top_k, temperature, cfg_lambda,
-                     coupling, 0, seed & 0xFFFFFFFFFFFFFFFF)
+                     coupling, sjd_mix, seed & 0xFFFFFFFFFFFFFFFF)
 
 
 def workspace_bytes(cfg):

@@ -389,6 +389,7 @@ __global__ __launch_bounds__(THREADS) void slice_kernel(const RowArgs a, const i
 // ---------------------------------------------------------------------------------
 struct RowOut {      // what a path hands to the common tail
   bool accept;
+  bool prace;         // the row makes a Gumbel-max draw from p (GS kernels only)
   float px, qx;
   float best;         // residual race (on rejection)
   int best_id;
@@ -400,16 +401,37 @@ struct RowOut {      // what a path hands to the common tail
 // (Alg. GS / Alg. SCD(pi_GS)): argmax_v(log p_v + G_v) with G_v = -ln(-ln U_v) is the
 // argmin of -ln(U_v) / p_v (appendix proof of the Gumbel-coupling theorem).  U_v is keyed by
 // (seed, sequence, position, id) only -- not by the iteration -- so that every iteration
-// redraws the position with the same noise.  Ties go to the lowest id.
-__device__ __forceinline__ void gumbel_entry(RowOut& out, uint2 key, uint32_t w3, int j, int v, float pv) {
-  const uint4 rr = philox4x32_10(make_uint4(static_cast<uint32_t>(v >> 2), static_cast<uint32_t>(j), 0u,
-                                            w3 | kStreamGumbel), key);
+// redraws the position with the same noise (w3s = stream 3, it = 0).  The independent redraft
+// of the alpha-coupling is the same draw with fresh noise (stream 5, it = the iteration).
+// Ties go to the lowest id.
+__device__ __forceinline__ void gumbel_entry(RowOut& out, uint2 key, uint32_t w3s, int j, int it,
+                                             int v, float pv) {
+  const uint4 rr = philox4x32_10(make_uint4(static_cast<uint32_t>(v >> 2), static_cast<uint32_t>(j),
+                                            static_cast<uint32_t>(it), w3s), key);
   const uint32_t lanes[4] = {rr.x, rr.y, rr.z, rr.w};
   const float sc = __fdiv_rn(-logf(u01(lanes[v & 3])), pv);
   if (sc < out.gbest || (sc == out.gbest && v < out.gbest_id)) {
     out.gbest = sc;
     out.gbest_id = v;
   }
+}
+
+// Which Gumbel-max draw from p the row makes for its next draft, if any (uniform over the
+// workgroup).  alpha-coupling (Sec. 5.3): with probability 1 - alpha the redraft is independent:
+// fresh noise.  Otherwise the shared-noise draw under pi_GS, and none under pi_MC (the MRS output
+// is the redraft).
+struct PRace {
+  bool on;
+  uint32_t w3s;
+  int it;
+};
+__device__ __forceinline__ PRace p_race_of_row(const RowArgs& a, uint2 key, uint32_t w3, int j, int it) {
+  if (a.alpha < 1.0f) {
+    const uint4 rs = philox4x32_10(make_uint4(0u, static_cast<uint32_t>(j), static_cast<uint32_t>(it),
+                                              w3 | kStreamAlpha), key);
+    if (!(u01(rs.x) <= a.alpha)) return {true, w3 | kStreamIndep, it};
+  }
+  return {a.gumbel != 0, w3 | kStreamGumbel, 0};
 }
 
 // Everything after the candidates sit in registers: threshold (if top-k filters),
@@ -529,21 +551,25 @@ __device__ __forceinline__ bool finish_regs(const RowArgs& a, const RowRef& R, c
   out.best_id = 0x7FFFFFFF;
   out.gbest = INFINITY;
   out.gbest_id = 0x7FFFFFFF;
-  if (GS) {                        // every row: next draft should the row survive
-    if (compact) {
+  if (GS) {                        // next draft should the row survive
+    const PRace pr = p_race_of_row(a, key, w3, j, R.it);
+    out.prace = pr.on;
+    if (pr.on) {
+      if (compact) {
 #pragma unroll
-      for (int q = 0; q < KPT; ++q)
-        if (rid[q] >= 0) {
-          const float pv = expf(rz[q] - lse_c);
-          if (pv > 0.f) gumbel_entry(out, key, w3, j, rid[q], pv);
-        }
-    } else {
+        for (int q = 0; q < KPT; ++q)
+          if (rid[q] >= 0) {
+            const float pv = expf(rz[q] - lse_c);
+            if (pv > 0.f) gumbel_entry(out, key, pr.w3s, j, pr.it, rid[q], pv);
+          }
+      } else {
 #pragma unroll
-      for (int e = 0; e < PER; ++e)
-        if (kept[e]) {
-          const float pv = expf(zv[e] - lse_c);
-          if (pv > 0.f) gumbel_entry(out, key, w3, j, vid[e], pv);
-        }
+        for (int e = 0; e < PER; ++e)
+          if (kept[e]) {
+            const float pv = expf(zv[e] - lse_c);
+            if (pv > 0.f) gumbel_entry(out, key, pr.w3s, j, pr.it, vid[e], pv);
+          }
+      }
     }
   }
   if (out.accept) return true;     // uniform over the workgroup
@@ -826,10 +852,14 @@ __device__ __forceinline__ void full_path(const RowArgs& a, const RowRef& R, uns
   out.gbest = INFINITY;
   out.gbest_id = 0x7FFFFFFF;
   if (GS) {
-    for_each_candidate([&](int v, uint32_t) {
-      const float pv = prob(zc[v], thr, lse_c);
-      if (pv > 0.f) gumbel_entry(out, key, w3, j, v, pv);
-    });
+    const PRace pr = p_race_of_row(a, key, w3, j, R.it);
+    out.prace = pr.on;
+    if (pr.on) {
+      for_each_candidate([&](int v, uint32_t) {
+        const float pv = prob(zc[v], thr, lse_c);
+        if (pv > 0.f) gumbel_entry(out, key, pr.w3s, j, pr.it, v, pv);
+      });
+    }
   }
   if (!out.accept) {
     for_each_candidate([&](int v, uint32_t) {
@@ -1019,7 +1049,8 @@ __global__ __launch_bounds__(THREADS) void row_kernel(const RowArgs a, const int
         gi = sm.s_id[w];
       }
     }
-    g_out = gi != 0x7FFFFFFF ? gi : R.x;   // empty support cannot happen (the maximum is kept)
+    // empty support cannot happen (the maximum is kept); -1: the row made no such draw
+    g_out = out.prace ? (gi != 0x7FFFFFFF ? gi : R.x) : -1;
   }
   if (a.mode != kRowRing) {
     if (tid == 0) {
@@ -1068,9 +1099,9 @@ __global__ __launch_bounds__(THREADS) void row_kernel(const RowArgs a, const int
   if (tid < live) {
     const size_t sidx = static_cast<size_t>(b) * a.L + (p0 + tid) % a.L;
     if (tid >= acc) {
-      // survivors: the MRS output is the coupled redraft (pi_MC); under pi_GS the redraft
-      // is the shared-noise Gumbel draw from the new distribution
-      a.X[sidx] = GS ? gg : yy;
+      // survivors: the MRS output is the coupled redraft (pi_MC); under pi_GS, or when the
+      // alpha-coupling switch chose the independent redraft, it is the row's Gumbel-max draw
+      a.X[sidx] = (GS && gg >= 0) ? gg : yy;
       a.age_w[sidx] += 1;
     } else {
       const int np = p0 + a.L + tid;
@@ -1132,7 +1163,7 @@ hipError_t launch_row(const RowArgs& a_in, hipStream_t s) {
     }
     configured = lds;
   }
-  if (a.gumbel && a.g && a.mode != kRowSelectOnly)
+  if ((a.gumbel || a.alpha < 1.0f) && a.g && a.mode != kRowSelectOnly)
     hipLaunchKernelGGL(row_kernel<true>, dim3(a.rows), dim3(THREADS), lds, s, a, P, capE);
   else
     hipLaunchKernelGGL(row_kernel<false>, dim3(a.rows), dim3(THREADS), lds, s, a, P, capE);

@@ -31,7 +31,7 @@ bool valid_config(const scd_config* c) {
   if (c->top_k < 0) return false;
   if (!(c->temperature > 0.f) || !std::isfinite(c->temperature)) return false;
   if (!std::isfinite(c->cfg_lambda)) return false;
-  if (c->reserved != 0) return false;
+  if (!(c->sjd_mix >= 0.f && c->sjd_mix <= 1.f)) return false;
   if (c->coupling < 0) return false;
   return true;
 }
@@ -107,6 +107,7 @@ int run_tail(scd_ctx* c, void* st) {
   if (c->n <= scd::kRowKernelMaxN) {
     // one fused launch: select + softmax + MRS per row, commit by each sequence's last row
     scd::RowArgs ra{};
+    ra.alpha = 1.0f;
     ra.mode = scd::kRowRing;
     ra.z_cur = field<float>(c, st, SCD_F_Z);
     ra.parity_stride = half;
@@ -133,6 +134,7 @@ int run_tail(scd_ctx* c, void* st) {
     ra.v_lo = c->cfg.v_lo; ra.seed = c->cfg.seed;
     ra.cand_base = static_cast<char*>(c->ws) + small_need(c->cfg);
     ra.gumbel = c->cfg.coupling == SCD_COUPLING_GS;
+    ra.alpha = 1.0f - c->cfg.sjd_mix;
     ra.g = field<int32_t>(c, st, SCD_F_G);
     return hip_rc(scd::launch_row(ra, c->stream));
   }
@@ -200,7 +202,8 @@ int scd_create(scd_ctx** out, const scd_config* cfg, void* d_workspace, size_t w
   if (!out || !valid_config(cfg)) return SCD_EINVAL;
   if (cfg->coupling != SCD_COUPLING_MC && cfg->coupling != SCD_COUPLING_GS) return SCD_EUNSUPPORTED;
   // the Gumbel draw lives in the fused row kernel only
-  if (cfg->coupling == SCD_COUPLING_GS && cfg->v_hi - cfg->v_lo > scd::kRowKernelMaxN)
+  if ((cfg->coupling == SCD_COUPLING_GS || cfg->sjd_mix > 0.f) &&
+      cfg->v_hi - cfg->v_lo > scd::kRowKernelMaxN)
     return SCD_EUNSUPPORTED;
   if (!d_workspace || !aligned(d_workspace, kAlign) || workspace_bytes < workspace_need(*cfg))
     return SCD_EWORKSPACE;
@@ -268,6 +271,7 @@ int scd_select(scd_ctx* c, const float* d_z, int32_t rows, float* d_thr, float* 
   if (!c || !d_z || rows < 0 || !d_thr || !d_lse || !d_nkept) return SCD_EINVAL;
   if (c->n <= scd::kRowKernelMaxN) {
     scd::RowArgs ra{};
+    ra.alpha = 1.0f;
     ra.mode = scd::kRowSelectOnly;
     ra.z_cur = d_z; ra.thr = d_thr; ra.lse = d_lse; ra.nkept = d_nkept;
     ra.rows = rows;
@@ -299,6 +303,7 @@ int scd_couple_draft(scd_ctx* c, const float* d_z_cur, const float* d_z_prev, co
   if (int rc = scd_select(c, d_z_prev, rows, thr_p, lse_p, nk_p); rc != SCD_OK) return rc;
   if (c->n <= scd::kRowKernelMaxN) {
     scd::RowArgs ra{};
+    ra.alpha = 1.0f;
     ra.mode = scd::kRowPlain;
     ra.z_cur = d_z_cur; ra.z_prev = d_z_prev;
     ra.thr = thr_c; ra.lse = lse_c; ra.nkept = nk_c;

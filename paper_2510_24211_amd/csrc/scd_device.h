@@ -10,7 +10,9 @@ namespace scd {
 
 constexpr int kWave = 64;
 
-enum : uint32_t { kStreamInit = 0, kStreamAccept = 1, kStreamResid = 2, kStreamGumbel = 3 };
+enum : uint32_t {
+  kStreamInit = 0, kStreamAccept = 1, kStreamResid = 2, kStreamGumbel = 3, kStreamAlpha = 4, kStreamIndep = 5
+};
 
 __device__ __forceinline__ uint4 philox4x32_10(uint4 c, uint2 k) {
 #pragma unroll

@@ -97,7 +97,10 @@ struct RowArgs {
   // Gumbel-sharing coupling: with gumbel != 0 and g non-null every row also draws
   // g = argmax_v(log p_v + G_v(position)) and the survivors' next drafts are g, not y
   int gumbel;
-  int32_t* g;            // [B, L] window order
+  // alpha-coupling: with alpha < 1 a row whose switch uniform exceeds alpha draws its redraft
+  // independently from p (same race, noise keyed by the iteration too) and reports it in g
+  float alpha;           // 1 => never
+  int32_t* g;            // [B, L] window order; -1 where the row made no such draw
   int rows;              // select-only: rows; else B*L
   int B, L, N, n, top_k, v_lo;
   uint64_t seed;

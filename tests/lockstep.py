@@ -28,19 +28,24 @@ def bf16_tensor(bits_np, device):
 
 
 class LockStep:
-    def __init__(self, w: wl.Workload, device="cuda:0", check_logits=True, coupling="mc"):
+    def __init__(self, w: wl.Workload, device="cuda:0", check_logits=True, coupling="mc", sjd_mix=0.0):
         self.w = w
         self.device = device
         self.check_logits = check_logits
         self.coupling = coupling
         self.cfg_c = B.config_from_workload(w)
         self.cfg_c.coupling = B.COUPLING_GS if coupling == "gs" else B.COUPLING_MC
+        self.cfg_c.sjd_mix = sjd_mix
+        # the library's alpha is fl32(1 - sjd_mix); the oracle gets exactly that number
+        alpha = float(np.float32(1.0) - np.float32(self.cfg_c.sjd_mix))
+        self.has_g = coupling == "gs" or sjd_mix > 0
         self.gpu = B.Scd(self.cfg_c, device)
         self.state = self.gpu.alloc_state()
         self.gpu.reset(self.state)
         self.ocfg = oscd.ScdConfig(B=w.B, L=w.L, N=w.N, V=w.V, v_lo=w.v_lo, v_hi=w.v_hi,
                                    top_k=w.top_k, temperature=w.temperature,
-                                   cfg_lambda=w.cfg_lambda, seed=w.seed, coupling=coupling)
+                                   cfg_lambda=w.cfg_lambda, seed=w.seed, coupling=coupling,
+                                   alpha=alpha)
         self.oracle = oscd.ScdOracle(self.ocfg)
         self.n = w.n_allowed
         if w.d > 0:
@@ -195,7 +200,7 @@ class LockStep:
                 elif r["k"] == 0 and int(gy[b, s]) != r["y"]:
                     assert r["flag_resid"], f"residual token differs on an unflagged draw b={b} s={s}"
                     res_ov[key] = int(gy[b, s])
-                if self.coupling == "gs":
+                if "g" in r:
                     st["flag_gs"] += r["flag_gs"]
                     if int(gg[b, s]) != r["g"]:
                         assert r["flag_gs"], f"Gumbel draw differs on an unflagged draw b={b} s={s}"
@@ -216,11 +221,11 @@ class LockStep:
             for s in range(L):
                 if s < lives[b]:
                     assert int(gk[b, s]) == res[b][s]["k"] and int(gy[b, s]) == res[b][s]["y"]
-                    if self.coupling == "gs":
-                        assert int(gg[b, s]) == res[b][s]["g"]
+                    if self.has_g:      # -1 where the row made no Gumbel-max draw
+                        assert int(gg[b, s]) == res[b][s].get("g", -1)
                 else:
                     assert int(gk[b, s]) == 1 and int(gy[b, s]) == -1
-                    if self.coupling == "gs":
+                    if self.has_g:
                         assert int(gg[b, s]) == -1
 
         # ---- commit --------------------------------------------------------

@@ -61,6 +61,8 @@ def test_create_rejects_bad_arguments_without_touching_the_device():
     assert lib.scd_create(None, ctypes.byref(cfg), fake, need, None) == B.SCD_EINVAL
     bad = B.make_config(B=1, L=8, N=64, V=1024, coupling=2)           # no such coupling
     assert lib.scd_create(ctypes.byref(ctx), ctypes.byref(bad), fake, need, None) == B.SCD_EUNSUPPORTED
+    neg = B.make_config(B=1, L=8, N=64, V=1024, sjd_mix=1.5)           # probability outside [0, 1]
+    assert lib.scd_create(ctypes.byref(ctx), ctypes.byref(neg), fake, need, None) == B.SCD_EINVAL
     big = B.make_config(B=1, L=8, N=64, V=70000, coupling=B.COUPLING_GS)   # GS: rows <= 65536 ids
     assert lib.scd_create(ctypes.byref(ctx), ctypes.byref(big), fake, 1 << 40, None) == B.SCD_EUNSUPPORTED
     assert lib.scd_create(ctypes.byref(ctx), ctypes.byref(cfg), fake, need, None) == B.SCD_OK

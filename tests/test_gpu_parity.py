@@ -274,6 +274,22 @@ def test_lockstep_gs_C1_full_and_C2_prefix():
     _lockstep(wl.WORKLOADS["C2"], max_steps=25, coupling="gs")
 
 
+@pytest.mark.parametrize("coupling,sjd_mix,kw", [
+    ("mc", 1.0, dict(N=64, L=8, seed=0)),                      # vanilla SJD: every redraft independent
+    ("mc", 0.5, dict(N=50, L=16, seed=33, top_k=64)),
+    ("gs", 0.25, dict(N=70, L=8, seed=34, B=3, V=1000)),
+    ("mc", 0.7, dict(N=20, L=4, seed=35, V=65536, top_k=2000, age_cap=4)),   # candidate path
+])
+def test_lockstep_alpha_coupling_toy_variants(coupling, sjd_mix, kw):
+    ls, st = _lockstep(wl.scaled(wl.WORKLOADS["C0"], name="toy-alpha", **kw), coupling=coupling,
+                       sjd_mix=sjd_mix)
+    assert st["adopt_gs"] <= max(2, 1e-3 * st["draws"])
+
+
+def test_lockstep_alpha_coupling_C2_prefix():
+    _lockstep(wl.WORKLOADS["C2"], max_steps=20, coupling="mc", sjd_mix=0.5)
+
+
 def test_gs_redraft_is_stable_where_mc_is_not_required_to_be():
     # p == q bit for bit (ages past the cap): the Gumbel draft of a position repeats exactly,
     # iteration after iteration, because its noise does not depend on the iteration.
