@@ -50,6 +50,12 @@ struct TrueT { static constexpr bool value = true; };
 struct FalseT { static constexpr bool value = false; };
 
 __device__ __forceinline__ void compiler_fence() { asm volatile("" ::: "memory"); }
+// Also a boundary for the machine scheduler, which otherwise treats loads of never-written
+// global memory as freely movable and may sink a prefetch down to its use.
+__device__ __forceinline__ void hard_fence() {
+  asm volatile("" ::: "memory");
+  __builtin_amdgcn_sched_barrier(0);
+}
 
 // Which rows of W (= columns of z) a workgroup works on.  Workgroup ids go round robin over
 // the 8 XCDs.  Read bandwidth on this chip is markedly higher when every XCD keeps to its own
@@ -337,6 +343,172 @@ __global__ __launch_bounds__((Cfg<RBW, C, NWV>::THREADS)) void lm_head_kernel(
   epilogue<RBW, C>(a, acc, nLb, nRB, rb0, mapped_row(rm, xcd, jt, K::BN, wave * 32 + ln), lg);
 }
 
+// Scheduling pattern "one MFMA, then its share of OPS memory-side operations (LDS reads, LDS
+// writes, global loads)", NM times: the counts must be compile-time constants.
+template <int M, int NM, int OPS>
+struct Interleave {
+  static __device__ __forceinline__ void run() {
+    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+    __builtin_amdgcn_sched_group_barrier(0x320, (OPS * (M + 1)) / NM - (OPS * M) / NM, 0);
+    Interleave<M + 1, NM, OPS>::run();
+  }
+};
+template <int NM, int OPS>
+struct Interleave<NM, NM, OPS> {
+  static __device__ __forceinline__ void run() {}
+};
+
+// ---- exactly 4 row blocks (B * ceil(L / 32) = 4, e.g. 2 sequences x 64 positions or one window
+// of 128): one workgroup holds ALL rows, so W is read exactly once and nothing depends on L2 --------
+// With 128-256 h rows per byte of W the matrix pipe and the LDS carry real load; the kernels above
+// re-stage the whole h tile for every 128 columns.  Here a workgroup of 8 wavefronts owns 256
+// columns x all 4 row blocks (half the LDS writes of h per column), tiled 4 x 2: wavefront (wc, wr)
+// multiplies 64 columns by 2 row blocks (6 operand reads per 8 MFMAs).  W and h tiles are shared,
+// double buffered in LDS, fetched ahead into registers by all 512 threads, one barrier per k-tile;
+// inside a wavefront the operand reads of k-step kk + 1, the LDS writes of the next tile and the
+// global loads of the tile after it are issued one by one between the MFMAs of k-step kk.
+template <int C>
+struct Gemm8Cfg {
+  static constexpr int THREADS = 512;
+  static constexpr int RBW = 4;
+  static constexpr int BN = 256;
+  static constexpr int HROWS = RBW * C * 32;
+  static constexpr int NB = 2 * C;                 // h-row tiles per wavefront (2 row blocks)
+  static constexpr int WL = BN * 8 / THREADS;      // 4
+  static constexpr int HL = HROWS * 8 / THREADS;   // 4 (C = 2) or 2
+  static constexpr int W_LDS = BN * PITCH;
+  static constexpr int H_LDS = HROWS * PITCH;
+  static constexpr int LDS_BYTES = 2 * (W_LDS + H_LDS) * 2;
+};
+
+template <int C>
+__global__ __launch_bounds__(512) void lm_head_gemm8_kernel(const LmHeadArgs a, const int nLb,
+                                                            const int nRB, const int VT) {
+  using K = Gemm8Cfg<C>;
+  constexpr int NB = K::NB, WL = K::WL, HL = K::HL, KK = BK / 16;
+  __shared__ __attribute__((aligned(16))) unsigned char lds_raw[K::LDS_BYTES];
+  uint16_t* const Ws_all = reinterpret_cast<uint16_t*>(lds_raw);
+  uint16_t* const Hs_all = Ws_all + 2 * K::W_LDS;
+
+  const int vt = blockIdx.x;
+  if (vt >= VT) return;
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  const int wc = wave & 3, wr = wave >> 2;
+  const int ln = lane & 31, lg = lane >> 5;
+  const int chunk = tid & 7, trow = tid >> 3;          // row 0..63 of a 64-row pass
+  const int d = a.d;
+  const int KT = (d + BK - 1) / BK;
+  const int rot = (vt * 5) % KT;
+  const uint32_t kclamp = static_cast<uint32_t>(d - 8) * 2u;
+
+  const char* const Wb = reinterpret_cast<const char*>(a.W);
+  const char* const Hb = reinterpret_cast<const char*>(a.h);
+  uint32_t woff[WL], hoff[HL];
+  bool hok[HL];
+#pragma unroll
+  for (int i = 0; i < WL; ++i)
+    woff[i] = static_cast<uint32_t>(min(vt * K::BN + trow + 64 * i, a.n - 1)) * static_cast<uint32_t>(d) * 2u;
+#pragma unroll
+  for (int i = 0; i < HL; ++i) {                       // tile row = 64 * i + trow
+    const int blk = 2 * i + (trow >> 5);
+    const int rb = blk / C, c = blk % C;
+    const int b = rb / nLb, s = (rb % nLb) * 32 + (trow & 31);
+    hok[i] = rb < nRB && s < a.L;
+    hoff[i] = hok[i] ? static_cast<uint32_t>((b * C + c) * a.L + s) * static_cast<uint32_t>(d) * 2u : 0u;
+  }
+  u32x4 wreg[1][WL], hreg[1][HL];   // one stage: a second one would not fit 256 registers
+  bool kok[1];
+  auto gload = [&](int stage, int t) {
+    int kt = min(t, KT - 1) + rot;
+    if (kt >= KT) kt -= KT;
+    const int k = kt * BK + chunk * 8;
+    kok[stage] = t < KT && k < d;                      // a tile past the end counts as zeros
+    const uint32_t kb = min(static_cast<uint32_t>(k) * 2u, kclamp);
+#pragma unroll
+    for (int i = 0; i < WL; ++i) wreg[stage][i] = *reinterpret_cast<const u32x4*>(Wb + (woff[i] + kb));
+#pragma unroll
+    for (int i = 0; i < HL; ++i) hreg[stage][i] = *reinterpret_cast<const u32x4*>(Hb + (hoff[i] + kb));
+  };
+  auto lstore = [&](int stage, int buf) {
+    uint16_t* const Wd = Ws_all + buf * K::W_LDS;
+    uint16_t* const Hd = Hs_all + buf * K::H_LDS;
+#pragma unroll
+    for (int i = 0; i < WL; ++i)
+      *reinterpret_cast<u32x4*>(&Wd[(trow + 64 * i) * PITCH + chunk * 8]) = wreg[stage][i];
+#pragma unroll
+    for (int i = 0; i < HL; ++i) {
+      const bool keep = hok[i] && kok[stage];
+      *reinterpret_cast<u32x4*>(&Hd[(trow + 64 * i) * PITCH + chunk * 8]) =
+          keep ? hreg[stage][i] : u32x4{0u, 0u, 0u, 0u};
+    }
+  };
+  f32x16 acc[2][NB];
+#pragma unroll
+  for (int c = 0; c < 2; ++c)
+#pragma unroll
+    for (int i = 0; i < NB; ++i)
+#pragma unroll
+      for (int j = 0; j < 16; ++j) acc[c][i][j] = 0.f;
+
+  // tile t: registers <- memory during tile t - 2; LDS buffer t % 2 <- registers during tile
+  // t - 1; MFMAs during tile t.  The barrier that ends tile t - 1 publishes it.
+  gload(0, 0);
+  lstore(0, 0);
+  gload(0, 1);
+  __syncthreads();
+  for (int t = 0; t < KT; t += 2) {            // an odd KT is padded by one all-zero tile
+#pragma unroll
+    for (int u = 0; u < 2; ++u) {              // tile t + u sits in buffer u
+      hard_fence();
+      const uint16_t* const Wt = Ws_all + u * K::W_LDS + (wc * 64 + ln) * PITCH + lg * 8;
+      const uint16_t* const Ht = Hs_all + u * K::H_LDS + (wr * NB * 32 + ln) * PITCH + lg * 8;
+      u32x4 bq[2][2], aq[2][NB];
+      auto fetch = [&](int q, int kk) {
+#pragma unroll
+        for (int c = 0; c < 2; ++c) bq[q][c] = *reinterpret_cast<const u32x4*>(&Wt[c * 32 * PITCH + kk * 16]);
+#pragma unroll
+        for (int i = 0; i < NB; ++i) aq[q][i] = *reinterpret_cast<const u32x4*>(&Ht[i * 32 * PITCH + kk * 16]);
+      };
+      fetch(0, 0);
+      lstore(0, u ^ 1);                        // tile t + u + 1 -> the other buffer
+      gload(0, t + u + 2);
+#pragma unroll
+      for (int kk = 0; kk < KK; ++kk) {
+        if (kk + 1 < KK) fetch((kk + 1) & 1, kk + 1);
+#pragma unroll
+        for (int c = 0; c < 2; ++c)
+#pragma unroll
+          for (int i = 0; i < NB; ++i)
+            acc[c][i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, aq[kk & 1][i]),
+                                                                __builtin_bit_cast(bf16x8, bq[kk & 1][c]),
+                                                                acc[c][i], 0, 0, 0);
+      }
+      // first the operands of k-step 0, then one memory-side operation between two MFMAs
+      constexpr int OPS = 2 * (WL + HL) + (KK - 1) * (NB + 2), NM = KK * 2 * NB;
+      __builtin_amdgcn_sched_group_barrier(0x100, NB + 2, 0);
+      Interleave<0, NM, OPS>::run();
+      hard_fence();
+      __syncthreads();
+    }
+  }
+
+#pragma unroll
+  for (int c = 0; c < 2; ++c) {
+    const int v = vt * K::BN + wc * 64 + c * 32 + ln;
+    if (v >= a.n) continue;
+#pragma unroll
+    for (int r2 = 0; r2 < 2; ++r2) {
+      const int rb = wr * 2 + r2;
+      if (rb >= nRB) break;
+      const RowBlockDst r = row_block_dst(a, rb, nLb);
+#pragma unroll
+      for (int j = 0; j < 16; ++j)
+        store_logit<C>(a, r, r.sbase + (j >> 2) * 8 + lg * 4 + (j & 3), v, acc[c][r2 * C][j],
+                       acc[c][r2 * C + C - 1][j]);
+    }
+  }
+}
+
 // ---- narrow vocabularies: k split over the wavefronts of a workgroup ---------------------
 template <int RBW, int C, int KS>
 struct SplitCfg {
@@ -552,10 +724,20 @@ hipError_t launch_split(const LmHeadArgs& a, hipStream_t s) {
   return hipGetLastError();
 }
 
+template <int C>
+hipError_t launch_gemm8(const LmHeadArgs& a, hipStream_t s) {
+  using K = Gemm8Cfg<C>;
+  const int nLb = (a.L + 31) / 32;
+  const int VT = (a.n + K::BN - 1) / K::BN;
+  hipLaunchKernelGGL((lm_head_gemm8_kernel<C>), dim3(VT), dim3(K::THREADS), 0, s, a, nLb, a.B * nLb, VT);
+  return hipGetLastError();
+}
+
 // Which kernel serves a problem shape.
 struct Variant {
   bool split;   // lm_head_splitk_kernel (else lm_head_kernel)
   int rbw, nw;  // row blocks per workgroup; wavefronts (= k parts for the split kernel)
+  bool gemm8;   // lm_head_gemm8_kernel
 };
 Variant choose(const LmHeadArgs& a) {
   const int nRB = a.B * ((a.L + 31) / 32);
@@ -566,16 +748,20 @@ Variant choose(const LmHeadArgs& a) {
   // many row blocks: 2 per workgroup.  4 per workgroup would read W from L2 half as often, but
   // its 91 KB of LDS and ~390 registers allow one workgroup per CU, and with one wavefront per
   // SIMD the load / LDS / MFMA phases of a tile run back to back (C3: 98 us against 85 us).
-  if (nRB >= 4) return {false, 2, 4};
-  if (nRB >= 2) return {narrow, 2, 4};
-  if (narrow) return {true, 1, KT >= 48 ? 8 : 4};
+  // all rows in one workgroup when there are 3 or 4 row blocks and enough 256-column tiles to
+  // fill the chip
+  if ((nRB == 4 || nRB == 3) && (a.n + 255) / 256 >= 200) return {false, 4, 8, true};
+  if (nRB >= 4) return {false, 2, 4, false};
+  if (nRB >= 2) return {narrow, 2, 4, false};
+  if (narrow) return {true, 1, KT >= 48 ? 8 : 4, false};
   // wide vocabulary: 8 wavefronts share each h tile (halves the h traffic out of L2)
-  return {false, 1, (a.n + 255) / 256 >= 200 ? 8 : 4};
+  return {false, 1, (a.n + 255) / 256 >= 200 ? 8 : 4, false};
 }
 
 template <int C>
 hipError_t launch_c(const LmHeadArgs& a, hipStream_t s) {
   const Variant v = choose(a);
+  if (v.gemm8) return launch_gemm8<C>(a, s);
   if (v.split) {
     if (v.rbw == 2) return launch_split<2, C, 4>(a, s);
     return v.nw == 8 ? launch_split<1, C, 8>(a, s) : launch_split<1, C, 4>(a, s);
@@ -592,6 +778,7 @@ hipError_t launch_lm_head(const LmHeadArgs& a, hipStream_t s) {
 
 int lm_head_kernel_name(const LmHeadArgs& a, char* buf, size_t cap) {
   const Variant v = choose(a);
+  if (v.gemm8) return snprintf(buf, cap, "lm_head_gemm8_kernel<%d>", a.C);
   return snprintf(buf, cap, "%s<%d, %d, %d>", v.split ? "lm_head_splitk_kernel" : "lm_head_kernel",
                   v.rbw, a.C, v.nw);
 }

@@ -44,6 +44,10 @@ def _require_gpu_and_library():
     (1, 32, 8192, 1500, 5, 1400, 3.0, 1.0),     # G = 8, 8 k parts
     (2, 32, 4096, 2500, 7, 2407, 3.0, 1.0),     # G = 16, two row blocks per workgroup
     (4, 32, 4096, 1000, 0, 1000, 3.0, 1.0),     # G = 16 available but many row blocks: wide kernel
+    # exactly 4 (or 3) row blocks and a wide vocabulary: the all-rows-in-one-workgroup kernel
+    (2, 64, 256, 52000, 0, 52000, 3.0, 1.0),
+    (1, 100, 192, 51300, 5, 51290, 3.0, 1.0),   # ragged n, ragged L, odd number of k tiles
+    (3, 20, 136, 51210, 0, 51210, 0.0, 0.9),    # 3 row blocks, no CFG, d not a multiple of the k tile
 ])
 def test_lm_head_against_oracle(Bn, L, d, V, v_lo, v_hi, lam, tau):
     g = np.random.default_rng(hash((Bn, L, d, V)) % 2 ** 32)
