@@ -236,20 +236,29 @@ def test_lockstep_C1_full():
     _lockstep(wl.WORKLOADS["C1"], check_logits=False)
 
 
-def test_lockstep_C2_prefix():
-    _lockstep(wl.WORKLOADS["C2"], max_steps=40)
+def test_lockstep_C2_full():
+    # the benchmark's workload, the whole decode (404 iterations, 12863 rows)
+    ls, st = _lockstep(wl.WORKLOADS["C2"], check_logits=False)
+    assert ls.oracle.done() and st["steps"] == 404
+
+
+def test_lockstep_C2_prefix_with_logits():
+    _lockstep(wl.WORKLOADS["C2"], max_steps=12)
 
 
 def test_lockstep_C2_fullV_prefix():
     _lockstep(wl.WORKLOADS["C2-fullV"], max_steps=5)
+    _lockstep(wl.WORKLOADS["C2-fullV"], max_steps=40, check_logits=False)
 
 
 def test_lockstep_C3_prefix():
     _lockstep(wl.WORKLOADS["C3"], max_steps=4)
+    _lockstep(wl.WORKLOADS["C3"], max_steps=12, check_logits=False)
 
 
 def test_lockstep_C4_prefix():
     _lockstep(wl.WORKLOADS["C4"], max_steps=3)
+    _lockstep(wl.WORKLOADS["C4"], max_steps=12, check_logits=False)
 
 
 # ----------------------------------------- Gumbel-sharing coupling (pi_GS)
