@@ -13,6 +13,9 @@ FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
          # the method's fp32 roundings are part of its definition: no fused contraction
          "-ffp-contract=off",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+         # plain leading kernel arguments arrive in SGPRs at wavefront launch (the hot kernels put
+         # what their first loads need there); kernels keep a fallback prologue that loads them
+         "-mllvm", "-amdgpu-kernarg-preload-count=16",
          "-Wall", "-Wno-unused-function"]
 
 

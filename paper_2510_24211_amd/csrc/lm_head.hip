@@ -525,7 +525,12 @@ struct SplitCfg {
 
 template <int RBW, int C, int KS>
 __global__ __launch_bounds__((SplitCfg<RBW, C, KS>::THREADS)) void lm_head_splitk_kernel(
-    const LmHeadArgs a, const int nLb, const int nRB, const int VT, const int MT, const RowMap rm) {
+    // plain leading arguments: the hardware preloads them into SGPRs at wavefront launch, so the
+    // first loads do not wait for a fetch of the kernel-argument segment
+    const uint16_t* const W_, const uint16_t* const h_, const int d_, const int n_, const int L_,
+    const int nLb, const int nRB, const int MT, const int rm_gshift, const int rm_rot,
+    const LmHeadArgs a) {
+  const RowMap rm{rm_gshift, rm_rot};
   using K = SplitCfg<RBW, C, KS>;
   constexpr int NBLK = K::NBLK, HROWS = K::HROWS, D = K::D, DH = K::DH, NWAVE = K::NW;
   __shared__ __attribute__((aligned(16))) unsigned char lds_raw[K::LDS_BYTES];
@@ -533,11 +538,11 @@ __global__ __launch_bounds__((SplitCfg<RBW, C, KS>::THREADS)) void lm_head_split
   const int xcd = id % 8, jt = id / (8 * MT);
   const int vt = jt * 8 + xcd;
   const int mt = (id / 8) % MT;
-  if (mapped_row(rm, xcd, jt, 32, 0) >= a.n) return;   // no row left for this tile
+  if (mapped_row(rm, xcd, jt, 32, 0) >= n_) return;   // no row left for this tile
   const int rb0 = mt * RBW;
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int ln = lane & 31, lg = lane >> 5, chunk = lane & 7, lrow = lane >> 3;
-  const int d = a.d;
+  const int d = d_;
   const int KT = (d + BK - 1) / BK;
   const int ktq = (KT + NWAVE - 1) / NWAVE;
   const int kt_begin = wave * ktq;
@@ -553,14 +558,14 @@ __global__ __launch_bounds__((SplitCfg<RBW, C, KS>::THREADS)) void lm_head_split
   uint16_t* const Ws = reinterpret_cast<uint16_t*>(lds_raw) + wave * (32 + HROWS) * PITCH;
   uint16_t* const Hs = Ws + 32 * PITCH;
 
-  const char* const Wb = reinterpret_cast<const char*>(a.W);
-  const char* const Hb = reinterpret_cast<const char*>(a.h);
+  const char* const Wb = reinterpret_cast<const char*>(W_);
+  const char* const Hb = reinterpret_cast<const char*>(h_);
   const uint32_t kclamp = static_cast<uint32_t>(d - 8) * 2u;
   uint32_t woff[4];
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
     const int v = mapped_row(rm, xcd, jt, 32, lrow + 8 * i);
-    woff[i] = static_cast<uint32_t>(min(v, a.n - 1)) * static_cast<uint32_t>(d) * 2u;
+    woff[i] = static_cast<uint32_t>(min(v, n_ - 1)) * static_cast<uint32_t>(d) * 2u;
   }
   constexpr int HL = HROWS / 8;                  // loads per lane per h tile
   uint32_t hoff[HL];
@@ -571,8 +576,8 @@ __global__ __launch_bounds__((SplitCfg<RBW, C, KS>::THREADS)) void lm_head_split
     const int blk = rr >> 5, r = rr & 31;
     const int rb = rb0 + blk / C, c = blk % C;
     const int b = rb / nLb, s = (rb % nLb) * 32 + r;
-    hok[i] = rb < nRB && s < a.L;
-    hoff[i] = hok[i] ? static_cast<uint32_t>((b * C + c) * a.L + s) * static_cast<uint32_t>(d) * 2u : 0u;
+    hok[i] = rb < nRB && s < L_;
+    hoff[i] = hok[i] ? static_cast<uint32_t>((b * C + c) * L_ + s) * static_cast<uint32_t>(d) * 2u : 0u;
   }
   u32x4 wreg[D][4], hreg[DH][HL];
   bool hkok[DH];
@@ -719,8 +724,8 @@ hipError_t launch_split(const LmHeadArgs& a, hipStream_t s) {
   const int MT = (nRB + RBW - 1) / RBW;
   int JT;
   const RowMap rm = make_row_map(a, 32, VT, true, &JT);
-  hipLaunchKernelGGL((lm_head_splitk_kernel<RBW, C, KS>), dim3(JT * 8 * MT), dim3(K::THREADS), 0, s, a, nLb,
-                     nRB, VT, MT, rm);
+  hipLaunchKernelGGL((lm_head_splitk_kernel<RBW, C, KS>), dim3(JT * 8 * MT), dim3(K::THREADS), 0, s, a.W, a.h,
+                     a.d, a.n, a.L, nLb, nRB, MT, rm.gshift, rm.rot, a);
   return hipGetLastError();
 }
 

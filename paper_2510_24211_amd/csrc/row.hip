@@ -255,7 +255,11 @@ struct RowRef {
   size_t widx, oidx;
 };
 
-__device__ __forceinline__ RowRef locate_row(const RowArgs& a, int r) {
+// pos, iter, mode, L, N repeat a.pos, a.iter, mode, L, N: the kernels receive them as plain
+// leading arguments, which the hardware preloads into SGPRs at wavefront launch, so that the first
+// dependent load (pos[b]) does not wait for a fetch of the kernel-argument segment.
+__device__ __forceinline__ RowRef locate_row(const RowArgs& a, int r, const int32_t* pos,
+                                             const int32_t* iter, int mode, int L, int N) {
   RowRef R{};
   R.widx = r;
   R.oidx = r;
@@ -263,24 +267,24 @@ __device__ __forceinline__ RowRef locate_row(const RowArgs& a, int r) {
   R.x = -1;
   R.active = true;
   const int n = a.n;
-  if (a.mode == kRowSelectOnly) {
+  if (mode == kRowSelectOnly) {
     R.zc = a.z_cur + static_cast<size_t>(r) * n;
     return R;
   }
-  R.b = r / a.L;
-  R.s = r % a.L;
-  R.p0 = a.pos[R.b];
-  R.live = max(0, min(a.L, a.N - R.p0));
-  R.widx = static_cast<size_t>(R.b) * a.L + R.s;
+  R.b = r / L;
+  R.s = r % L;
+  R.p0 = pos[R.b];
+  R.live = max(0, min(L, N - R.p0));
+  R.widx = static_cast<size_t>(R.b) * L + R.s;
   if (R.s >= R.live) {
     R.active = false;
     return R;
   }
-  if (a.mode == kRowRing) {
-    R.it = a.iter[R.b];
+  if (mode == kRowRing) {
+    R.it = iter[R.b];
     const int par = R.it & 1;
-    const size_t sidx = static_cast<size_t>(R.b) * a.L + (R.p0 + R.s) % a.L;
-    const size_t half = static_cast<size_t>(a.B) * a.L;
+    const size_t sidx = static_cast<size_t>(R.b) * L + (R.p0 + R.s) % L;
+    const size_t half = static_cast<size_t>(a.B) * L;
     R.oidx = par * half + sidx;
     R.x = a.x[sidx];
     R.fresh = a.age[sidx] == 0;
@@ -307,14 +311,16 @@ __device__ __forceinline__ RowRef locate_row(const RowArgs& a, int r) {
 // ---------------------------------------------------------------------------------
 // slice kernel
 // ---------------------------------------------------------------------------------
-__global__ __launch_bounds__(THREADS) void slice_kernel(const RowArgs a, const int P, const int capE,
-                                                        const int rank) {
+__global__ __launch_bounds__(THREADS) void slice_kernel(const int32_t* const pos_, const int32_t* const iter_,
+                                                        const int mode_, const int L_, const int N_,
+                                                        const int P, const int capE, const int rank,
+                                                        const RowArgs a) {
   __shared__ uint32_t hist[NBINS];
   __shared__ uint32_t arr[NBINS];
   __shared__ Small sm;
   const int tid = threadIdx.x;
   const int r = blockIdx.x / P, p = blockIdx.x % P;
-  const RowRef R = locate_row(a, r);
+  const RowRef R = locate_row(a, r, pos_, iter_, mode_, L_, N_);
   if (!R.active) return;
   const int n = a.n;
   const int slice_len = (((n + P - 1) / P) + 3) & ~3;
@@ -922,13 +928,15 @@ __device__ __forceinline__ void direct_path(const RowArgs& a, const RowRef& R, u
 }
 
 template <bool GS>
-__global__ __launch_bounds__(THREADS) void row_kernel(const RowArgs a, const int P, const int capE) {
+__global__ __launch_bounds__(THREADS) void row_kernel(const int32_t* const pos_, const int32_t* const iter_,
+                                                      const int mode_, const int L_, const int N_,
+                                                      const int P, const int capE, const RowArgs a) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   __shared__ Small sm;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int n = a.n;
   const int r = blockIdx.x;
-  const RowRef R = locate_row(a, r);
+  const RowRef R = locate_row(a, r, pos_, iter_, mode_, L_, N_);
   if (!R.active) {
     if (tid == 0) {
       a.y[R.widx] = -1;
@@ -1149,7 +1157,8 @@ hipError_t launch_row(const RowArgs& a_in, hipStream_t s) {
     a.cand = reinterpret_cast<uint2*>(base);
     a.cand_cnt = reinterpret_cast<uint32_t*>(base + pairs);
     a.cand_cut = reinterpret_cast<uint32_t*>(base + pairs + small_block(a.rows));
-    hipLaunchKernelGGL(slice_kernel, dim3(a.rows * P), dim3(THREADS), 0, s, a, P, capE, rank);
+    hipLaunchKernelGGL(slice_kernel, dim3(a.rows * P), dim3(THREADS), 0, s, a.pos, a.iter, a.mode, a.L, a.N, P,
+                       capE, rank, a);
     if (hipError_t e = hipGetLastError(); e != hipSuccess) return e;
   }
   const size_t lds = lds_bytes_for(a.n);
@@ -1164,9 +1173,11 @@ hipError_t launch_row(const RowArgs& a_in, hipStream_t s) {
     configured = lds;
   }
   if ((a.gumbel || a.alpha < 1.0f) && a.g && a.mode != kRowSelectOnly)
-    hipLaunchKernelGGL(row_kernel<true>, dim3(a.rows), dim3(THREADS), lds, s, a, P, capE);
+    hipLaunchKernelGGL(row_kernel<true>, dim3(a.rows), dim3(THREADS), lds, s, a.pos, a.iter, a.mode, a.L, a.N, P,
+                       capE, a);
   else
-    hipLaunchKernelGGL(row_kernel<false>, dim3(a.rows), dim3(THREADS), lds, s, a, P, capE);
+    hipLaunchKernelGGL(row_kernel<false>, dim3(a.rows), dim3(THREADS), lds, s, a.pos, a.iter, a.mode, a.L, a.N, P,
+                       capE, a);
   return hipGetLastError();
 }
 

@@ -108,7 +108,8 @@ class LockStep:
         else:
             z = self.toy.window(i_b, ages)                         # [B, L, n] fp32
             self.gpu.step_logits(torch.from_numpy(z).to(self.device), self.state)
-            z_rows = [lg.process_logits(z[b, :lives[b]], None, 0.0, w.temperature)
+            # scd_step_logits takes logits that are already processed: no guidance mix, no 1/tau
+            z_rows = [lg.process_logits(z[b, :lives[b]], None, 0.0, 1.0)
                       if lives[b] else None for b in range(Bn)]
         rc, flags = self.gpu.status(self.state)
         assert rc == B.SCD_OK, (rc, flags)

@@ -209,6 +209,9 @@ def test_lockstep_C0_full_and_golden():
     dict(N=300, L=128, seed=17, V=512),             # window longer than a wavefront
     dict(N=12, L=4, seed=18, V=70000, top_k=500, age_cap=4),   # rows too long for the LDS-resident kernel
     dict(N=20, L=4, seed=19, V=65536, top_k=2000, age_cap=4),  # longest row of the LDS-resident kernel
+    dict(N=600, L=256, seed=20, V=256, age_cap=6),             # the longest window the library takes
+    dict(N=40, L=8, seed=28, V=777, top_k=5000),               # top_k above the vocabulary: no filter
+    dict(N=30, L=8, seed=29, V=2, B=2),                        # two-id vocabulary
 ])
 def test_lockstep_toy_variants(kw):
     _lockstep(wl.scaled(wl.WORKLOADS["C0"], name="toy", **kw))
@@ -226,6 +229,11 @@ def test_lockstep_scaled_cfg_masked_batched():
     # C3-like: CFG, unaligned allowed range, 4 sequences that finish at different iterations
     _lockstep(wl.scaled(wl.WORKLOADS["C3"], name="C3s", B=4, N=80, V=4096, d=256, v_lo=4, v_hi=1028,
                         top_k=250))
+
+
+def test_lockstep_scaled_cfg_temperature():
+    _lockstep(wl.scaled(wl.WORKLOADS["C2"], name="C2t", N=64, V=4096, d=320, v_lo=100, v_hi=3000,
+                        top_k=300, temperature=0.8))
 
 
 def test_lockstep_scaled_video():
