@@ -1,11 +1,11 @@
 """LM head and logit post-processing (oracle side; test infrastructure only).
 
-The paper defines p^(t) as "the final distribution after all logit
-post-processing (top-k, CFG)" (Sec. 4.3, last sentence).  The processors and
+p^(t) is the distribution that remains once every logit processor (top-k,
+guidance) has been applied (Sec. 4.3, last sentence).  The processors and
 their parameters come from Sec. 5.1 "Effect on CFG" (mixed logit
 (1+lambda)*c - lambda*u) and the appendix "Experimental Details" (temperature
-tau = 1, top-k K = 2000 / 1000).  The order used here is
-    LM head -> CFG combine -> allowed-id mask -> 1/tau -> top-k -> softmax.
+tau = 1, top-k K = 2000 / 1000, nucleus p = 0.8 for video).  The order used here is
+    LM head -> CFG combine -> allowed-id mask -> 1/tau -> top-k -> top-p -> softmax.
 
 Precision: the LM head accumulates in fp64 over the exact bf16 input values and
 rounds the logit once to fp32.  The three fp32 roundings of the CFG combine and
@@ -71,6 +71,25 @@ def topk_threshold(z, top_k):
     return np.float32(srt[top_k - 1])
 
 
+def nucleus_threshold(z, keep, top_p):
+    """Nucleus (top-p) filter (appendix "Experimental Details", video generation:
+    p = 0.8, applied to the distribution that the earlier processors leave):
+    among the ids of `keep`, ordered by decreasing probability, the shortest
+    prefix whose probabilities sum to at least top_p survives; ids tied with the
+    last survivor survive too (the filter is a threshold on the logit, so equal
+    logits are never split).  Returns that threshold as fp32 (the smallest
+    surviving logit); -inf when the filter is off (top_p <= 0 or >= 1).  fp64."""
+    if not (0.0 < top_p < 1.0):
+        return np.float32(-np.inf)
+    zs = np.sort(np.asarray(z, dtype=np.float32)[keep].astype(np.float64))[::-1]
+    pr = np.exp(zs - zs[0])
+    pr = pr / pr.sum()
+    cum = np.cumsum(pr)
+    reach = np.nonzero(cum >= top_p)[0]
+    last = reach[0] if reach.size else zs.size - 1     # rounding may leave cum[-1] just below 1
+    return np.float32(zs[last])
+
+
 def softmax_kept(z, thr):
     """Probability row p_v = [z_v >= thr] * exp(z_v - m) / sum_kept exp(z_w - m),
     fp64.  Also returns the log normaliser lse = m + log(sum)."""
@@ -82,8 +101,11 @@ def softmax_kept(z, thr):
     return e / s, m + np.log(s)
 
 
-def distribution(z, top_k):
-    """(p fp64 row, thr fp32, lse fp64) for a processed-logit row."""
+def distribution(z, top_k, top_p=0.0):
+    """(p fp64 row, thr fp32, lse fp64) for a processed-logit row: top-k first,
+    then the nucleus filter on what top-k left."""
+    z = np.asarray(z, dtype=np.float32)
     thr = topk_threshold(z, top_k)
+    thr = max(thr, nucleus_threshold(z, z >= thr, top_p))
     p, lse = softmax_kept(z, thr)
-    return p, thr, lse
+    return p, np.float32(thr), lse

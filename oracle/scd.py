@@ -67,6 +67,7 @@ class ScdConfig:
     v_lo: int = 0
     v_hi: int = -1           # -1 => V
     top_k: int = 0           # 0 => off
+    top_p: float = 0.0       # nucleus mass; 0 (or >= 1) => off
     temperature: float = 1.0
     cfg_lambda: float = 0.0  # 0 => no CFG
     seed: int = 0
@@ -96,14 +97,26 @@ def _ambiguous_ids(z, thr, top_k, tol_z):
     return ids if ids.size > 1 else np.zeros(0, dtype=np.int64)
 
 
+def _ambiguous_nucleus_ids(z, keep, top_p, tol_mass):
+    """Ids whose membership in the nucleus could flip if the cumulative masses
+    were off by tol_mass (relative to the total): those between the thresholds
+    for top_p + tol_mass and top_p - tol_mass."""
+    if not (0.0 < top_p < 1.0):
+        return np.zeros(0, dtype=np.int64)
+    t_in = lg.nucleus_threshold(z, keep, max(top_p - tol_mass, np.finfo(np.float64).tiny))
+    t_out = lg.nucleus_threshold(z, keep, min(top_p + tol_mass, 1.0 - 1e-16))
+    return np.nonzero(keep & (z >= t_out) & (z < t_in))[0]
+
+
 class ScdOracle:
     """State machine of the vectorised form.  One step = evaluate() (turn the
     processed-logit rows of the window into distributions), sample() (one MRS
     per window position) and commit() (emit, slide, re-initialise)."""
 
-    def __init__(self, cfg: ScdConfig, tol=1e-5):
+    def __init__(self, cfg: ScdConfig, tol=1e-5, tol_mass=2e-6):
         self.cfg = cfg
         self.tol = tol
+        self.tol_mass = tol_mass              # nucleus boundary: relative error of a cumulative mass
         B, L, N = cfg.B, cfg.L, cfg.N
         self.i = [0] * B                      # accepted-prefix pointer
         self.t = [0] * B                      # iterations done (= NFE)
@@ -143,7 +156,9 @@ class ScdOracle:
     def evaluate(self, z_rows, keep_override=None):
         """z_rows[b]: fp32 [Lw_b, |A|] processed logits of the window
         (after CFG, mask, temperature).  Returns plan[b][s] =
-        dict(p, thr, lse, nkept, ambiguous)."""
+        dict(p, thr, lse, nkept, ambiguous).  thr is the smallest kept logit when a
+        filter removed something, else -inf.  keep_override[(b, position)] = {id: kept}
+        forces the membership of ids listed as ambiguous (top-k stage, then nucleus stage)."""
         cfg = self.cfg
         plan = []
         for b in range(cfg.B):
@@ -159,8 +174,20 @@ class ScdOracle:
                 ov = (keep_override or {}).get((b, i + s))
                 if ov:
                     for v, kv in ov.items():
-                        assert v in amb, "membership override outside the ambiguous set"
-                        keep[v] = kv
+                        if v in amb:
+                            keep[v] = kv
+                if 0.0 < cfg.top_p < 1.0:
+                    thr_p = lg.nucleus_threshold(z, keep, cfg.top_p)
+                    amb_p = _ambiguous_nucleus_ids(z, keep, cfg.top_p, self.tol_mass)
+                    keep = keep & (z >= thr_p)
+                    if ov:
+                        for v, kv in ov.items():
+                            if v in amb_p:
+                                keep[v] = kv
+                    thr = np.float32(z[keep].min())
+                    amb = np.union1d(amb, amb_p)
+                if ov:
+                    assert all(v in amb for v in ov), "membership override outside the ambiguous set"
                 z64 = z.astype(np.float64)
                 m = z64[keep].max()
                 e = np.where(keep, np.exp(z64 - m), 0.0)
@@ -334,7 +361,7 @@ def decode_sequential(cfg: ScdConfig, model, tol=1e-5):
             z = model(b, i, Lw, toks, t, ages)
             for s in range(Lw):
                 j = i + s
-                p_new[j], _, _ = lg.distribution(z[s], cfg.top_k)
+                p_new[j], _, _ = lg.distribution(z[s], cfg.top_k, cfg.top_p)
                 t_new[j] = t
                 age[j] = age.get(j, 0) + 1
             # Verify, sequentially, break at the first rejection

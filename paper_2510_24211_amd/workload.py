@@ -39,6 +39,7 @@ class Workload:
     temperature: float = 1.0
     cfg_lambda: float = 0.0
     seed: int = 0
+    top_p: float = 0.0      # nucleus mass, 0 => off
     amp: float = 0.3
     decay: float = 0.6
     age_cap: int = 16
@@ -80,6 +81,9 @@ WORKLOADS = {
     # Video-shaped: 8 frames x 40x40, L=64.
     "C4": Workload("C4", B=2, L=64, N=12800, V=64000, d=4096, top_k=2000,
                    cfg_lambda=3.0, seed=4, decay=0.7, age_cap=24, frames=8),
+    # The same video shape with the nucleus filter p = 0.8 in place of top-k.
+    "C4-topp": Workload("C4-topp", B=2, L=64, N=12800, V=64000, d=4096, top_p=0.8,
+                        cfg_lambda=3.0, seed=4, decay=0.7, age_cap=24, frames=8),
 }
 
 

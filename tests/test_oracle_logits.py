@@ -108,3 +108,83 @@ def test_lse_consistency():
     keep = z >= thr
     np.testing.assert_allclose(p[keep], np.exp(z[keep].astype(np.float64) - lse), rtol=1e-12)
     assert np.all(p[~keep] == 0)
+
+
+# ---- nucleus (top-p) filter ---------------------------------------------------------
+def _probs_to_logits(p):
+    return np.log(np.asarray(p, dtype=np.float64)).astype(np.float32)
+
+
+def test_nucleus_hand_worked_rows():
+    # probabilities 0.5, 0.3, 0.15, 0.05 (any order of ids): cumulative 0.5, 0.8, 0.95, 1
+    z = _probs_to_logits([0.15, 0.5, 0.05, 0.3])
+    every = np.ones(4, dtype=bool)
+    kept = lambda p: set(np.nonzero(z >= lg.nucleus_threshold(z, every, p))[0])
+    assert kept(0.4) == {1}                 # the mode alone already holds 0.5
+    assert kept(0.6) == {1, 3}
+    assert kept(0.9) == {0, 1, 3}
+    assert kept(0.96) == {0, 1, 2, 3}
+    # off outside (0, 1)
+    assert lg.nucleus_threshold(z, every, 0.0) == -np.inf
+    assert lg.nucleus_threshold(z, every, 1.0) == -np.inf
+
+
+def test_nucleus_brute_force_minimal_top_set():
+    """Definition by exhaustion with rational arithmetic on small integer weights
+    (probability = weight / total): over all sets that are closed upwards in probability
+    (a kept id implies every more probable id and every id tied with it), the smallest one
+    with mass >= p.  Targets closer than 1e-5 to a cumulative mass are skipped: the logits are
+    ln(weight) rounded to fp32, so the row's probabilities are the weights only to ~1e-7."""
+    g = np.random.default_rng(5)
+    checked = 0
+    for trial in range(200):
+        n = int(g.integers(2, 8))
+        w = g.integers(1, 9, size=n)                      # ties are frequent
+        z = np.log(w.astype(np.float64)).astype(np.float32)
+        total = Fraction(int(w.sum()))
+        p = Fraction(int(g.integers(1, 64)), 64)
+        levels = sorted(set(int(x) for x in w), reverse=True)
+        masses = [Fraction(int(w[w >= lv].sum())) / total for lv in levels]
+        if any(abs(float(m - p)) < 1e-5 for m in masses):
+            continue
+        best = next(set(np.nonzero(w >= lv)[0]) for lv, m in zip(levels, masses) if m >= p)
+        thr = lg.nucleus_threshold(z, np.ones(n, dtype=bool), float(p))
+        assert set(np.nonzero(z >= thr)[0]) == best
+        checked += 1
+    assert checked > 100
+
+
+def test_nucleus_invariants_and_order_with_topk():
+    g = np.random.default_rng(6)
+    for _ in range(20):
+        n = 200
+        z = (g.standard_normal(n) * 2.5).astype(np.float32)
+        top_p = float(g.uniform(0.05, 0.95))
+        p_full = special.softmax(z.astype(np.float64))
+        thr = lg.nucleus_threshold(z, np.ones(n, dtype=bool), top_p)
+        kept = z >= thr
+        assert p_full[kept].sum() >= top_p - 1e-12                       # enough mass
+        weakest = p_full[kept].min()
+        assert p_full[kept].sum() - weakest * (p_full[kept] == weakest).sum() < top_p + 1e-12   # minimal
+        assert p_full[kept].min() >= p_full[~kept].max() if (~kept).any() else True   # most probable ids
+        # against the library: sort, cumulative sum, searchsorted
+        order = np.argsort(-p_full, kind="stable")
+        cut = int(np.searchsorted(np.cumsum(p_full[order]), top_p, side="left"))
+        assert kept.sum() == cut + 1                                     # no ties in this row
+        # after top-k the nucleus is taken on the RENORMALISED top-k distribution
+        K = 20
+        pk, thr_k, _ = lg.distribution(z, K, 0.0)
+        pkp, thr_kp, _ = lg.distribution(z, K, top_p)
+        order_k = np.argsort(-pk, kind="stable")
+        cut_k = int(np.searchsorted(np.cumsum(pk[order_k]), top_p, side="left"))
+        assert (pkp > 0).sum() == cut_k + 1 and thr_kp >= thr_k
+        assert abs(pkp.sum() - 1.0) < 1e-12
+        np.testing.assert_allclose(pkp[pkp > 0], pk[pkp > 0] / pk[pkp > 0].sum(), rtol=1e-12)
+
+
+def test_nucleus_ties_are_never_split():
+    z = _probs_to_logits([0.4, 0.2, 0.2, 0.2])
+    thr = lg.nucleus_threshold(z, np.ones(4, dtype=bool), 0.5)    # 0.4 + one of the 0.2s would do
+    assert (z >= thr).sum() == 4
+    thr = lg.nucleus_threshold(z, np.ones(4, dtype=bool), 0.3)
+    assert (z >= thr).sum() == 1

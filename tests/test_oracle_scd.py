@@ -37,7 +37,7 @@ class ToyContextModel:
     def __call__(self, b, i, Lw, toks, t, age):
         return np.stack([self.tab[tuple(int(x) for x in toks[: i + s])] for s in range(Lw)])
 
-    def ar_joint(self, top_k=0):
+    def ar_joint(self, top_k=0, top_p=0.0):
         J = {}
         for seq in itertools.product(range(self.V), repeat=self.N):
             pr = 1.0
@@ -46,19 +46,26 @@ class ToyContextModel:
                 if top_k:
                     thr = np.sort(z)[::-1][top_k - 1]
                     z = np.where(z >= thr, z, -np.inf)
-                pr *= special.softmax(z)[seq[j]]
+                pz = special.softmax(z)
+                if top_p:          # nucleus: most probable ids until their mass reaches top_p
+                    order = np.argsort(-pz)
+                    ncut = int(np.searchsorted(np.cumsum(pz[order]), top_p)) + 1
+                    keep = np.zeros(self.V, dtype=bool)
+                    keep[order[:ncut]] = True
+                    pz = np.where(keep, pz, 0.0) / pz[keep].sum()
+                pr *= pz[seq[j]]
             J[seq] = pr
         return J
 
 
-def _joint_test(L, top_k, runs, seed0):
+def _joint_test(L, top_k, runs, seed0, top_p=0.0):
     V, N = 3, 3
     model = ToyContextModel(V, N, seed=7)
-    want = model.ar_joint(top_k)
+    want = model.ar_joint(top_k, top_p)
     counts = {k: 0 for k in want}
     nfe = 0
     for r in range(runs):
-        cfg = ScdConfig(B=1, L=L, N=N, V=V, top_k=top_k, seed=seed0 + r)
+        cfg = ScdConfig(B=1, L=L, N=N, V=V, top_k=top_k, top_p=top_p, seed=seed0 + r)
         o = scd.decode(cfg, model)
         counts[tuple(int(x) for x in o.out[0])] += 1
         nfe += o.t[0]
@@ -88,12 +95,20 @@ def test_end_to_end_lossless_with_topk():
     assert p > 1e-4
 
 
+def test_end_to_end_lossless_with_nucleus():
+    """The nucleus filter changes the target distribution, nothing else: the decode samples
+    the autoregressive model whose every conditional is cut to its most probable ids holding
+    60 % of the mass (computed here with sort / cumsum / searchsorted)."""
+    p, _ = _joint_test(L=3, top_k=0, runs=8000, seed0=1300000, top_p=0.6)
+    assert p > 1e-4
+
+
 # --------------------------------------------------------------------------
 def _toy(name="C0", **kw):
     w = wl.scaled(wl.WORKLOADS[name], **kw)
     toy = wl.ToyLogits(w)
     cfg = ScdConfig(B=w.B, L=w.L, N=w.N, V=w.V, v_lo=w.v_lo, v_hi=w.v_hi, top_k=w.top_k,
-                    temperature=w.temperature, cfg_lambda=0.0, seed=w.seed)
+                    top_p=w.top_p, temperature=w.temperature, cfg_lambda=0.0, seed=w.seed)
 
     def model(b, i, Lw, toks, t, age):
         return np.stack([toy.table[b, i + s, min(int(age[s]), w.age_cap)] for s in range(Lw)])
@@ -123,7 +138,8 @@ def test_identical_distributions_accept_everything():
 
 def test_vectorised_equals_sequential_on_C0_and_small_cases():
     cases = [_toy(), _toy(N=37, L=5, seed=3), _toy(N=20, L=1, seed=4), _toy(N=9, L=16, seed=5),
-             _toy(N=30, L=8, seed=6, top_k=50), _toy(N=24, L=4, seed=8, B=3)]
+             _toy(N=30, L=8, seed=6, top_k=50), _toy(N=24, L=4, seed=8, B=3),
+             _toy(N=30, L=8, seed=9, top_p=0.8), _toy(N=30, L=8, seed=10, top_k=50, top_p=0.5)]
     for w, cfg, model in cases:
         o = scd.decode(cfg, model)
         out, nfe, hist = scd.decode_sequential(cfg, model)
