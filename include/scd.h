@@ -77,6 +77,13 @@ typedef struct scd_config {
   float sjd_mix;       /* 1 - alpha of the alpha-coupling (Sec. 5.3): probability that a
                           redraft is an independent draw from p instead of the coupled one;
                           0 = SCD (default), 1 = vanilla SJD; must be in [0, 1]          */
+  float top_p;         /* nucleus filter (appendix "Experimental Details", video setting
+                          p = 0.8), applied to the distribution that top-k leaves: of the ids
+                          in order of decreasing probability the shortest prefix whose mass
+                          reaches top_p is kept, ids tied with its last member included;
+                          0 or 1 => off; must be in [0, 1]; needs v_hi - v_lo <= 65536.
+                          Decided on 2^-40 fixed-point masses of expf(z - max), exactly:
+                          mass above an id * 2^24 < round(top_p * 2^24) * total mass          */
   uint64_t seed;
 } scd_config;
 
@@ -107,7 +114,8 @@ typedef enum scd_field {
   SCD_F_K = 7,        /* uint8 [B, L]    last step's accept bits, window order         */
   SCD_F_PX = 8,       /* float [B, L]    last step's p(x), window order                */
   SCD_F_QX = 9,       /* float [B, L]    last step's q(x), window order                */
-  SCD_F_THR = 10,     /* float [2, B, L] top-k threshold per parity (t & 1) and slot   */
+  SCD_F_THR = 10,     /* float [2, B, L] smallest kept logit (top-k / nucleus threshold; -inf when
+                                         neither filters) per parity (t & 1) and slot  */
   SCD_F_LSE = 11,     /* float [2, B, L] log normaliser per parity and slot            */
   SCD_F_NKEPT = 12,   /* int32 [2, B, L] size of the kept set per parity and slot      */
   SCD_F_Z = 13,       /* float [2, B, L, n] processed logits per parity and slot       */

@@ -35,7 +35,7 @@ class ScdConfig(ctypes.Structure):
                 ("v_hi", ctypes.c_int32), ("top_k", ctypes.c_int32),
                 ("temperature", ctypes.c_float), ("cfg_lambda", ctypes.c_float),
                 ("coupling", ctypes.c_int32), ("sjd_mix", ctypes.c_float),
-                ("seed", ctypes.c_uint64)]
+                ("top_p", ctypes.c_float), ("seed", ctypes.c_uint64)]
 
 
 class ScdError(RuntimeError):
@@ -94,9 +94,9 @@ def strerror(code):
 
 
 def make_config(B, L, N, V, d=0, v_lo=0, v_hi=-1, top_k=0, temperature=1.0, cfg_lambda=0.0,
-                seed=0, coupling=0, sjd_mix=0.0):
+                seed=0, coupling=0, sjd_mix=0.0, top_p=0.0):
     return ScdConfig(B, L, N, V, d, v_lo, V if v_hi < 0 else v_hi, top_k, temperature, cfg_lambda,
-                     coupling, sjd_mix, seed & 0xFFFFFFFFFFFFFFFF)
+                     coupling, sjd_mix, top_p, seed & 0xFFFFFFFFFFFFFFFF)
 
 
 def workspace_bytes(cfg):
@@ -268,4 +268,4 @@ def device_copy(src, dst, stream=None):
 def config_from_workload(w):
     """ScdConfig for a paper_2510_24211_amd.workload.Workload."""
     return make_config(B=w.B, L=w.L, N=w.N, V=w.V, d=w.d, v_lo=w.v_lo, v_hi=w.v_hi, top_k=w.top_k,
-                       temperature=w.temperature, cfg_lambda=w.cfg_lambda, seed=w.seed)
+                       temperature=w.temperature, cfg_lambda=w.cfg_lambda, seed=w.seed, top_p=w.top_p)

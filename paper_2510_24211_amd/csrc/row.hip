@@ -71,6 +71,8 @@ struct Small {
   int s_id[NW];
   int last;
   int first_rej;
+  unsigned long long mtot[NW];   // nucleus: per-wavefront masses
+  unsigned long long sel_mass;
 };
 
 // key with -0 folded onto +0, so that key order == float order for non-NaNs
@@ -243,6 +245,126 @@ __device__ __forceinline__ uint32_t select_regs(const float (&zv)[PER], const ui
     width = 1ull << s2;
     if (s2 == 0) return lo;
   }
+}
+
+// ---------------------------------------------------------------------------------
+// Nucleus (top-p) filter (appendix "Experimental Details", video setting p = 0.8), applied
+// to the set K1 that top-k left:  keep v  iff  the mass of the ids with a LARGER logit is
+// below top_p times the mass of K1 -- the shortest most-probable prefix reaching top_p, ids
+// tied with its last member included.  Like top-k the result is a threshold on the logit.
+//   Masses are 64-bit fixed point, w_v = trunc(expf(z_v - m) * 2^40): integer sums do not
+//   depend on the order of the LDS atomics, so the decision is run-to-run identical, and it
+//   is taken exactly:  above(v) * 2^24 < P24 * S  with P24 = round(top_p * 2^24).
+//   Search: one histogram of masses over bins LINEAR in the logit (spreads a bell-shaped row
+//   over the bins), then radix levels over the key bits of the selected bin's members.
+// `each(f)` must call f(key, z) for every element of K1, the same elements on every call.
+// mh: NBINS_P 64-bit bins (the space of the count histogram).  Uniform over the workgroup.
+constexpr int NBINS_P = NBINS / 2;
+static_assert(NBINS_P % THREADS == 0 || THREADS % NBINS_P == 0, "nucleus: bins per thread");
+
+__device__ __forceinline__ unsigned long long mass_of(float z, float m) {
+  return static_cast<unsigned long long>(expf(z - m) * 1099511627776.0f);   // <= 2^40
+}
+
+__device__ __forceinline__ unsigned long long wave_inclusive_sum_u64(unsigned long long v, int lane) {
+  // three 24-bit limbs: 64 lanes x 2^24 stays inside an int
+  const int l0 = wave_inclusive_sum_i32(static_cast<int>(v & 0xFFFFFFull), lane);
+  const int l1 = wave_inclusive_sum_i32(static_cast<int>((v >> 24) & 0xFFFFFFull), lane);
+  const int l2 = wave_inclusive_sum_i32(static_cast<int>(v >> 48), lane);
+  return static_cast<unsigned long long>(static_cast<uint32_t>(l0)) +
+         (static_cast<unsigned long long>(static_cast<uint32_t>(l1)) << 24) +
+         (static_cast<unsigned long long>(static_cast<uint32_t>(l2)) << 48);
+}
+
+// ceil(P24 * S / 2^24) for S < 2^58
+__device__ __forceinline__ unsigned long long nucleus_target(unsigned long long S, uint32_t p24) {
+  const unsigned long long hi = (S >> 32) * p24, lo = (S & 0xFFFFFFFFull) * p24;
+  return (hi << 8) + ((lo + 0xFFFFFFull) >> 24);
+}
+
+// The bin b with  above + mass(bins > b) < target <= above + mass(bins >= b);  `above` grows
+// by mass(bins > b).  FIRST: target is derived here from the total mass of the histogram.
+template <bool FIRST>
+__device__ __forceinline__ uint32_t find_bin_mass(const unsigned long long* mh, unsigned long long& target,
+                                                  unsigned long long& above, uint32_t p24, Small& sm) {
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  constexpr int PER = NBINS_P >= THREADS ? NBINS_P / THREADS : 1;
+  unsigned long long c[PER], local = 0;
+#pragma unroll
+  for (int j = 0; j < PER; ++j) {
+    const int idx = tid * PER + j;                 // top bins first
+    c[j] = idx < NBINS_P ? mh[NBINS_P - 1 - idx] : 0ull;
+    local += c[j];
+  }
+  unsigned long long incl = wave_inclusive_sum_u64(local, lane);
+  if (lane == 63) sm.mtot[wave] = incl;
+  __syncthreads();
+  unsigned long long base = above, total = 0;
+#pragma unroll
+  for (int w = 0; w < NW; ++w) {
+    base += w < wave ? sm.mtot[w] : 0ull;
+    total += sm.mtot[w];
+  }
+  if (FIRST) target = nucleus_target(total, p24);
+  incl += base;
+  const unsigned long long excl = incl - local;
+  if (excl < target && target <= incl) {           // exactly one thread
+    unsigned long long ab = excl;
+#pragma unroll
+    for (int j = 0; j < PER; ++j) {
+      if (ab + c[j] >= target) {
+        sm.sel_bin = static_cast<uint32_t>(NBINS_P - 1 - (tid * PER + j));
+        sm.sel_mass = ab;
+        break;
+      }
+      ab += c[j];
+    }
+  }
+  __syncthreads();
+  const uint32_t bin = sm.sel_bin;
+  above = sm.sel_mass;
+  __syncthreads();
+  return bin;
+}
+
+template <class Each>
+__device__ __forceinline__ uint32_t nucleus_key(Each&& each, float m, float zmin, uint32_t p24,
+                                                unsigned long long* mh, Small& sm) {
+  const int tid = threadIdx.x;
+  // logits more than 110 below the maximum weigh nothing: they all go to bin 0
+  const float zlo = fmaxf(zmin, m - 110.f);
+  const float scale = (m > zlo) ? __fdiv_rn(static_cast<float>(NBINS_P - 1), m - zlo) : 0.f;
+  auto lin_bin = [&](float z) {
+    const float t = (z - zlo) * scale;
+    return t >= 0.f ? (t >= static_cast<float>(NBINS_P - 1) ? NBINS_P - 1 : static_cast<int>(t)) : 0;
+  };
+  auto zero = [&]() {
+    for (int i = tid; i < NBINS_P; i += THREADS) mh[i] = 0ull;
+  };
+  __syncthreads();                                  // earlier users of the histogram space are done
+  zero();
+  __syncthreads();
+  each([&](uint32_t key, float z) { atomicAdd(&mh[lin_bin(z)], mass_of(z, m)); });
+  __syncthreads();
+  unsigned long long target = 0, above = 0;
+  const int b1 = static_cast<int>(find_bin_mass<true>(mh, target, above, p24, sm));
+  // radix levels over the key bits of the members of bin b1
+  uint32_t lo = 0;
+  int s2 = 32;
+  while (s2 > 0) {
+    const int width_bits = s2;                      // candidates: keys in [lo, lo + 2^width_bits)
+    s2 = width_bits > 11 ? width_bits - 11 : 0;
+    zero();
+    __syncthreads();
+    each([&](uint32_t key, float z) {
+      if (lin_bin(z) == b1 && key >= lo &&
+          (width_bits == 32 || (key - lo) >> width_bits == 0u))
+        atomicAdd(&mh[(key - lo) >> s2], mass_of(z, m));
+    });
+    __syncthreads();
+    lo += find_bin_mass<false>(mh, target, above, p24, sm) << s2;
+  }
+  return lo;
 }
 
 // Where a kernel instance finds its row.
@@ -448,7 +570,7 @@ __device__ __forceinline__ PRace p_race_of_row(const RowArgs& a, uint2 key, uint
 // Otherwise (ids scattered over the row) the previous logits of the KEPT ids are gathered
 // here, right after the compaction, so that the round trip hides behind the normaliser and
 // the accept draw.  The LDS arrays cid / cz / cq hold ccap entries each.
-template <int PER, bool PREQ, bool GS>
+template <int PER, bool PREQ, bool GS, bool TOPP>
 __device__ __forceinline__ bool finish_regs(const RowArgs& a, const RowRef& R, const int (&vid)[PER],
                                             const float (&zv)[PER], const float (&zq)[PER],
                                             const bool (&ok)[PER], bool filter, uint32_t cut_max,
@@ -476,6 +598,18 @@ __device__ __forceinline__ bool finish_regs(const RowArgs& a, const RowRef& R, c
                                            cid, sm);
     if (tkey < cut_max) return false;     // an unseen logit could be >= the K-th candidate
     thr = key_to_float(tkey);
+  }
+  if (TOPP && a.top_p24 != 0u) {          // nucleus filter on what top-k left
+    const float thr_k = thr;
+    const float zmin = filter ? thr_k : (kmin <= kmax ? key_to_float(kmin) : m);
+    const uint32_t pkey = nucleus_key(
+        [&](auto&& f) {
+#pragma unroll
+          for (int e = 0; e < PER; ++e)
+            if (ok[e] && zv[e] >= thr_k) f(kv[e], zv[e]);
+        },
+        m, zmin, a.top_p24, reinterpret_cast<unsigned long long*>(hist), sm);
+    thr = key_to_float(pkey);
   }
   // Kept ids are a random ~K/n of each thread's logits; compacting them into LDS (count /
   // scan / write: a fixed order) lets the expensive per-id work that follows be dealt out
@@ -636,7 +770,7 @@ __device__ __forceinline__ bool finish_regs(const RowArgs& a, const RowRef& R, c
 // The complete in-place path: one coalesced read of the row, 16-bit key prefixes in
 // LDS, histogram select; then a candidate list in registers, or in-place scans when
 // top-k is off or the candidates do not fit.
-template <bool GS>
+template <bool GS, bool TOPP>
 __device__ __forceinline__ void full_path(const RowArgs& a, const RowRef& R, unsigned char* smem,
                                           float zcx, float zpx, Small& sm, RowOut& out) {
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -774,7 +908,7 @@ __device__ __forceinline__ void full_path(const RowArgs& a, const RowRef& R, uns
     for (int e = 0; e < PER_LIST; ++e) zq[e] = 0.f;
     // the prefixes in LDS are spent: their space takes the compaction arrays
     const int ccap = min(kKeptCap, static_cast<int>(static_cast<size_t>(n8) * 2 / 12));
-    finish_regs<PER_LIST, false, GS>(a, R, vid, zv, zq, ok, true, 0u, zcx, zpx, hist,
+    finish_regs<PER_LIST, false, GS, TOPP>(a, R, vid, zv, zq, ok, true, 0u, zcx, zpx, hist,
                           reinterpret_cast<uint32_t*>(smem), reinterpret_cast<float*>(smem) + ccap,
                           reinterpret_cast<float*>(smem) + 2 * ccap, ccap, sm, out);
     return;
@@ -811,6 +945,19 @@ __device__ __forceinline__ void full_path(const RowArgs& a, const RowRef& R, uns
       lowkey |= find_bin(hist, need_ab, sm) << shift;
     }
     thr = key_to_float((t16 << 16) | lowkey);
+  }
+  if (TOPP && a.top_p24 != 0u) {          // nucleus filter on what top-k left
+    const float thr_k = thr;
+    const float zmin = filter ? thr_k : key_to_float(p16min << 16);
+    const uint32_t pkey = nucleus_key(
+        [&](auto&& f) {
+          for_each_candidate([&](int v, uint32_t) {
+            const float z = zc[v];
+            if (z >= thr_k) f(zkey(z), z);
+          });
+        },
+        m, zmin, a.top_p24, reinterpret_cast<unsigned long long*>(hist), sm);
+    thr = key_to_float(pkey);
   }
   float sum = 0.f;
   int cnt = 0;
@@ -889,7 +1036,7 @@ __device__ __forceinline__ void full_path(const RowArgs& a, const RowRef& R, uns
 }
 
 // The whole row in registers, PER logits per thread (n <= PER * THREADS).
-template <int PER, bool GS>
+template <int PER, bool GS, bool TOPP>
 __device__ __forceinline__ void direct_path(const RowArgs& a, const RowRef& R, unsigned char* smem,
                                             bool filter, float zcx, float zpx, Small& sm, RowOut& out) {
   const int tid = threadIdx.x, n = a.n;
@@ -922,12 +1069,14 @@ __device__ __forceinline__ void direct_path(const RowArgs& a, const RowRef& R, u
     }
   }
   uint32_t* cid = hist + NBINS;
-  finish_regs<PER, true, GS>(a, R, vid, zv, zq, ok, filter, 0u, zcx, zpx, hist, cid,
+  finish_regs<PER, true, GS, TOPP>(a, R, vid, zv, zq, ok, filter, 0u, zcx, zpx, hist, cid,
                    reinterpret_cast<float*>(cid + kKeptCap),
                    reinterpret_cast<float*>(cid + 2 * kKeptCap), kKeptCap, sm, out);
 }
 
-template <bool GS>
+// GS: the row also makes a Gumbel-max draw from p; TOPP: the nucleus filter is compiled in
+// (kept out of the other instances: its live ranges cost the hot kernels registers)
+template <bool GS, bool TOPP>
 __global__ __launch_bounds__(THREADS) void row_kernel(const int32_t* const pos_, const int32_t* const iter_,
                                                       const int mode_, const int L_, const int N_,
                                                       const int P, const int capE, const RowArgs a) {
@@ -959,8 +1108,8 @@ __global__ __launch_bounds__(THREADS) void row_kernel(const int32_t* const pos_,
   bool done = false;
   if (n <= kDirectMaxN) {
     // ---- the whole row in registers ------------------------------------------------
-    if (n <= kDirectMaxN / 2) direct_path<PER_DIRECT / 2, GS>(a, R, smem, filter, zcx, zpx, sm, out);
-    else direct_path<PER_DIRECT, GS>(a, R, smem, filter, zcx, zpx, sm, out);
+    if (n <= kDirectMaxN / 2) direct_path<PER_DIRECT / 2, GS, TOPP>(a, R, smem, filter, zcx, zpx, sm, out);
+    else direct_path<PER_DIRECT, GS, TOPP>(a, R, smem, filter, zcx, zpx, sm, out);
     done = true;
   } else if (filter && a.cand && P > 0) {
     // ---- candidates emitted by the slice kernel ----------------------------------
@@ -1006,12 +1155,12 @@ __global__ __launch_bounds__(THREADS) void row_kernel(const int32_t* const pos_,
 #pragma unroll
       for (int e = 0; e < PER_LIST; ++e) zq[e] = 0.f;
       const int ccap = min(kKeptCap, static_cast<int>(static_cast<size_t>((n + 7) & ~7) * 2 / 12));
-      done = finish_regs<PER_LIST, false, GS>(a, R, vid, zv, zq, ok, true, cut_max, zcx, zpx, hist,
+      done = finish_regs<PER_LIST, false, GS, TOPP>(a, R, vid, zv, zq, ok, true, cut_max, zcx, zpx, hist,
                                    reinterpret_cast<uint32_t*>(smem), reinterpret_cast<float*>(smem) + ccap,
                                    reinterpret_cast<float*>(smem) + 2 * ccap, ccap, sm, out);
     }
   }
-  if (!done) full_path<GS>(a, R, smem, zcx, zpx, sm, out);
+  if (!done) full_path<GS, TOPP>(a, R, smem, zcx, zpx, sm, out);
   if (a.mode == kRowSelectOnly) return;
 
   // ---- winner of the race (lexicographic (score, id) minimum) -------------------
@@ -1164,20 +1313,21 @@ hipError_t launch_row(const RowArgs& a_in, hipStream_t s) {
   const size_t lds = lds_bytes_for(a.n);
   static size_t configured = 0;          // grows monotonically; benign if raced (idempotent call)
   if (lds > configured) {
-    for (const void* f : {reinterpret_cast<const void*>(row_kernel<false>),
-                          reinterpret_cast<const void*>(row_kernel<true>)}) {
+    for (const void* f : {reinterpret_cast<const void*>(row_kernel<false, false>),
+                          reinterpret_cast<const void*>(row_kernel<true, false>),
+                          reinterpret_cast<const void*>(row_kernel<false, true>),
+                          reinterpret_cast<const void*>(row_kernel<true, true>)}) {
       hipError_t e = hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize,
                                          static_cast<int>(lds));
       if (e != hipSuccess) return e;
     }
     configured = lds;
   }
-  if ((a.gumbel || a.alpha < 1.0f) && a.g && a.mode != kRowSelectOnly)
-    hipLaunchKernelGGL(row_kernel<true>, dim3(a.rows), dim3(THREADS), lds, s, a.pos, a.iter, a.mode, a.L, a.N, P,
-                       capE, a);
-  else
-    hipLaunchKernelGGL(row_kernel<false>, dim3(a.rows), dim3(THREADS), lds, s, a.pos, a.iter, a.mode, a.L, a.N, P,
-                       capE, a);
+  const bool gs = (a.gumbel || a.alpha < 1.0f) && a.g && a.mode != kRowSelectOnly;
+  const bool topp = a.top_p24 != 0u;
+  auto* const kernel = gs ? (topp ? row_kernel<true, true> : row_kernel<true, false>)
+                          : (topp ? row_kernel<false, true> : row_kernel<false, false>);
+  hipLaunchKernelGGL(kernel, dim3(a.rows), dim3(THREADS), lds, s, a.pos, a.iter, a.mode, a.L, a.N, P, capE, a);
   return hipGetLastError();
 }
 

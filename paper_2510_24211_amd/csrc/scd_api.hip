@@ -33,7 +33,16 @@ bool valid_config(const scd_config* c) {
   if (!std::isfinite(c->cfg_lambda)) return false;
   if (!(c->sjd_mix >= 0.f && c->sjd_mix <= 1.f)) return false;
   if (c->coupling < 0) return false;
+  if (!(c->top_p >= 0.f && c->top_p <= 1.f)) return false;
   return true;
+}
+
+// round(top_p * 2^24); 0 where the nucleus filter is off (top_p = 0 or 1, or so small that it
+// rounds to nothing: then the most probable id alone would be kept, which 1 expresses)
+uint32_t top_p24_of(const scd_config& c) {
+  if (!(c.top_p > 0.f && c.top_p < 1.f)) return 0u;
+  const long v = std::lround(static_cast<double>(c.top_p) * 16777216.0);
+  return static_cast<uint32_t>(v < 1 ? 1 : v);
 }
 
 Layout make_layout(const scd_config& c) {
@@ -131,6 +140,7 @@ int run_tail(scd_ctx* c, void* st) {
     ra.out = field<int32_t>(c, st, SCD_F_OUT);
     ra.rows = c->cfg.B * c->cfg.L;
     ra.B = c->cfg.B; ra.L = c->cfg.L; ra.N = c->cfg.N; ra.n = c->n; ra.top_k = c->cfg.top_k;
+    ra.top_p24 = top_p24_of(c->cfg);
     ra.v_lo = c->cfg.v_lo; ra.seed = c->cfg.seed;
     ra.cand_base = static_cast<char*>(c->ws) + small_need(c->cfg);
     ra.gumbel = c->cfg.coupling == SCD_COUPLING_GS;
@@ -202,6 +212,7 @@ int scd_create(scd_ctx** out, const scd_config* cfg, void* d_workspace, size_t w
   if (!out || !valid_config(cfg)) return SCD_EINVAL;
   if (cfg->coupling != SCD_COUPLING_MC && cfg->coupling != SCD_COUPLING_GS) return SCD_EUNSUPPORTED;
   // the Gumbel draw lives in the fused row kernel only
+  if (top_p24_of(*cfg) != 0u && cfg->v_hi - cfg->v_lo > scd::kRowKernelMaxN) return SCD_EUNSUPPORTED;
   if ((cfg->coupling == SCD_COUPLING_GS || cfg->sjd_mix > 0.f) &&
       cfg->v_hi - cfg->v_lo > scd::kRowKernelMaxN)
     return SCD_EUNSUPPORTED;
@@ -276,6 +287,7 @@ int scd_select(scd_ctx* c, const float* d_z, int32_t rows, float* d_thr, float* 
     ra.z_cur = d_z; ra.thr = d_thr; ra.lse = d_lse; ra.nkept = d_nkept;
     ra.rows = rows;
     ra.B = c->cfg.B; ra.L = c->cfg.L; ra.N = c->cfg.N; ra.n = c->n; ra.top_k = c->cfg.top_k;
+    ra.top_p24 = top_p24_of(c->cfg);
     if (rows <= c->cfg.B * c->cfg.L) ra.cand_base = static_cast<char*>(c->ws) + small_need(c->cfg);
     return hip_rc(scd::launch_row(ra, c->stream));
   }
@@ -313,6 +325,7 @@ int scd_couple_draft(scd_ctx* c, const float* d_z_cur, const float* d_z_prev, co
     ra.y = d_y; ra.k = d_k;
     ra.rows = rows;
     ra.B = c->cfg.B; ra.L = c->cfg.L; ra.N = c->cfg.N; ra.n = c->n; ra.top_k = c->cfg.top_k;
+    ra.top_p24 = top_p24_of(c->cfg);
     ra.v_lo = c->cfg.v_lo; ra.seed = c->cfg.seed;
     ra.cand_base = static_cast<char*>(c->ws) + small_need(c->cfg);
     return hip_rc(scd::launch_row(ra, c->stream));

@@ -103,6 +103,8 @@ struct RowArgs {
   int32_t* g;            // [B, L] window order; -1 where the row made no such draw
   int rows;              // select-only: rows; else B*L
   int B, L, N, n, top_k, v_lo;
+  // nucleus filter: round(top_p * 2^24), 0 => off.  Applied to what top-k left.
+  uint32_t top_p24;
   uint64_t seed;
   // scratch for the slice kernel (rows longer than 8192 ids): row_candidate_bytes(rows)
   // bytes of device memory, 256-byte aligned, or null (then rows are processed whole)

@@ -43,10 +43,12 @@ class LockStep:
         self.state = self.gpu.alloc_state()
         self.gpu.reset(self.state)
         self.ocfg = oscd.ScdConfig(B=w.B, L=w.L, N=w.N, V=w.V, v_lo=w.v_lo, v_hi=w.v_hi,
-                                   top_k=w.top_k, temperature=w.temperature,
+                                   top_k=w.top_k, top_p=w.top_p, temperature=w.temperature,
                                    cfg_lambda=w.cfg_lambda, seed=w.seed, coupling=coupling,
                                    alpha=alpha)
         self.oracle = oscd.ScdOracle(self.ocfg)
+        if w.d > 0:   # nucleus boundary: a cumulative mass moves by at most ~2 max|dz| of the LM head
+            self.oracle.tol_mass = 2e-6 + 4e-5 * (1 + 2 * abs(w.cfg_lambda))
         self.n = w.n_allowed
         if w.d > 0:
             W = wl.lm_head_weight(w)

@@ -28,8 +28,22 @@ def test_library_exports_every_declared_symbol():
         assert hasattr(lib, name), name
 
 
-def test_config_struct_matches_header_size():
-    assert ctypes.sizeof(B.ScdConfig) == 56
+def test_config_struct_matches_header_layout(tmp_path):
+    """sizeof / offsetof as the C compiler sees the header against the ctypes mirror."""
+    import os
+    import subprocess
+    fields = [name for name, _ in B.ScdConfig._fields_]
+    src = tmp_path / "layout.c"
+    src.write_text('#include <stdio.h>\n#include <stddef.h>\n#include "scd.h"\nint main(void) {\n'
+                   '  printf("%zu", sizeof(scd_config));\n' +
+                   "".join(f'  printf(" %zu", offsetof(scd_config, {f}));\n' for f in fields) +
+                   "  return 0;\n}\n")
+    inc = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "include")
+    exe = tmp_path / "layout"
+    subprocess.run(["gcc", "-I", inc, str(src), "-o", str(exe)], check=True)
+    got = [int(x) for x in subprocess.run([str(exe)], check=True, capture_output=True, text=True).stdout.split()]
+    assert got[0] == ctypes.sizeof(B.ScdConfig) == 64
+    assert got[1:] == [getattr(B.ScdConfig, f).offset for f in fields]
 
 
 def test_size_queries_validate_config():
@@ -65,6 +79,10 @@ def test_create_rejects_bad_arguments_without_touching_the_device():
     assert lib.scd_create(ctypes.byref(ctx), ctypes.byref(neg), fake, need, None) == B.SCD_EINVAL
     big = B.make_config(B=1, L=8, N=64, V=70000, coupling=B.COUPLING_GS)   # GS: rows <= 65536 ids
     assert lib.scd_create(ctypes.byref(ctx), ctypes.byref(big), fake, 1 << 40, None) == B.SCD_EUNSUPPORTED
+    wide = B.make_config(B=1, L=8, N=64, V=70000, top_p=0.8)          # nucleus: rows <= 65536 ids
+    assert lib.scd_create(ctypes.byref(ctx), ctypes.byref(wide), fake, 1 << 40, None) == B.SCD_EUNSUPPORTED
+    off = B.make_config(B=1, L=8, N=64, V=1024, top_p=1.25)            # mass outside [0, 1]
+    assert lib.scd_create(ctypes.byref(ctx), ctypes.byref(off), fake, need, None) == B.SCD_EINVAL
     assert lib.scd_create(ctypes.byref(ctx), ctypes.byref(cfg), fake, need, None) == B.SCD_OK
     # null pointers are refused before any launch
     assert lib.scd_lm_head(ctx, None, None, None) == B.SCD_EINVAL

@@ -74,9 +74,9 @@ def test_lm_head_against_oracle(Bn, L, d, V, v_lo, v_hi, lam, tau):
 
 
 # ------------------------------------------------------- select / softmax
-def _select_case(z, top_k):
+def _select_case(z, top_k, top_p=0.0):
     rows, n = z.shape
-    cfg = B.make_config(B=1, L=1, N=1, V=n, top_k=top_k)
+    cfg = B.make_config(B=1, L=1, N=1, V=n, top_k=top_k, top_p=top_p)
     s = B.Scd(cfg, DEV)
     thr = torch.empty(rows, device=DEV)
     lse = torch.empty(rows, device=DEV)
@@ -84,8 +84,19 @@ def _select_case(z, top_k):
     s.select(torch.from_numpy(z).to(DEV), rows, thr, lse, nk)
     torch.cuda.synchronize()
     thr, lse, nk = thr.cpu().numpy(), lse.cpu().numpy(), nk.cpu().numpy()
+    adopted = 0
     for r in range(rows):
-        p, thr_o, lse_o = lg.distribution(z[r], top_k)
+        p, thr_o, lse_o = lg.distribution(z[r], top_k, top_p)
+        if top_p and thr[r] != thr_o:
+            # the nucleus boundary is a comparison of fp sums: within 2e-6 of the target mass
+            # either side is right, and the GPU's threshold must be a logit of the row there
+            keep_k = z[r] >= lg.topk_threshold(z[r], top_k)
+            t_in = lg.nucleus_threshold(z[r], keep_k, top_p - 2e-6)
+            t_out = lg.nucleus_threshold(z[r], keep_k, top_p + 2e-6)
+            assert t_out <= thr[r] <= t_in and (z[r] == thr[r]).any(), (r, thr[r], thr_o, t_out, t_in)
+            thr_o = thr[r]
+            p, lse_o = lg.softmax_kept(z[r], thr_o)
+            adopted += 1
         assert thr[r] == thr_o, (r, thr[r], thr_o)                   # exact order statistic
         assert nk[r] == int((p > 0).sum()) or nk[r] == int((z[r] >= thr_o).sum())
         assert abs(float(lse[r]) - lse_o) <= 1e-6 * max(1.0, abs(lse_o))
@@ -93,6 +104,7 @@ def _select_case(z, top_k):
         keep = z[r] >= thr[r]
         pg = np.where(keep, np.exp(z[r].astype(np.float64) - float(lse[r])), 0.0)
         assert np.abs(pg - p).max() <= 1e-6
+    return adopted
 
 
 @pytest.mark.parametrize("n,top_k", [(1024, 0), (1024, 100), (1000, 1), (1000, 999), (1000, 1000),
@@ -107,6 +119,24 @@ def test_select_softmax_against_oracle(n, top_k):
         z[3] = -np.abs(z[3]) - 100                    # all negative, large magnitude
         z[4, :] = z[4, 0]                             # constant row
     _select_case(z, top_k)
+
+
+@pytest.mark.parametrize("n,top_k,top_p", [(1024, 0, 0.8), (1000, 100, 0.8), (1000, 0, 0.02), (1000, 0, 0.9999),
+                                           (8192, 2000, 0.8), (16384, 0, 0.8), (12000, 3000, 0.95),
+                                           (64000, 0, 0.8), (65536, 2000, 0.5), (40000, 0, 0.3),
+                                           (5, 0, 0.7), (2, 0, 0.5), (1, 0, 0.8), (4097, 33, 0.6)])
+def test_select_nucleus_against_oracle(n, top_k, top_p):
+    g = np.random.default_rng(n * 37 + top_k)
+    z = (g.standard_normal((7, n)) * 3).astype(np.float32)
+    if n >= 1000:
+        z[1, g.integers(0, n, 50)] = -np.inf          # masked-out ids inside the row
+        z[2] = np.round(z[2] * 4) / 4                 # heavy ties, also at the boundary
+        z[3] = -np.abs(z[3]) - 100                    # all negative, large magnitude
+        z[4, :] = z[4, 0]                             # constant row: every id tied, all kept
+        z[5] = z[5] * 2                               # peaked: the nucleus is a handful of ids
+        z[6] = z[6] * 0.05                            # flat: the nucleus is most of the row
+    adopted = _select_case(z, top_k, top_p)
+    assert adopted <= 2                               # boundary cases are rare
 
 
 # ------------------------------------------------------------- MRS stage
@@ -234,6 +264,25 @@ def test_lockstep_scaled_cfg_masked_batched():
 def test_lockstep_scaled_cfg_temperature():
     _lockstep(wl.scaled(wl.WORKLOADS["C2"], name="C2t", N=64, V=4096, d=320, v_lo=100, v_hi=3000,
                         top_k=300, temperature=0.8))
+
+
+@pytest.mark.parametrize("kw", [
+    dict(N=40, L=8, seed=30, V=1000, top_p=0.8),                   # 8 logits per thread, no top-k
+    dict(N=40, L=8, seed=31, V=12000, top_k=3000, top_p=0.9, age_cap=4),   # 16 per thread, after top-k
+    dict(N=12, L=4, seed=32, V=65536, top_p=0.8, age_cap=4),       # in-place path
+    dict(N=12, L=4, seed=33, V=40000, top_k=2000, top_p=0.5, age_cap=4),   # slice kernel + candidates
+    dict(N=30, L=8, seed=34, V=2000, top_p=0.999),                 # nearly everything kept
+    dict(N=30, L=8, seed=35, V=2000, top_p=0.001, B=2),            # the mode alone
+])
+def test_lockstep_nucleus_toy_variants(kw):
+    _lockstep(wl.scaled(wl.WORKLOADS["C0"], name="toy", **kw))
+
+
+def test_lockstep_nucleus_scaled_and_video_prefix():
+    _lockstep(wl.scaled(wl.WORKLOADS["C4-topp"], name="C4ps", N=8 * 24, V=2000, d=512, L=64))
+    _lockstep(wl.scaled(wl.WORKLOADS["C2"], name="C2p", N=64, V=4096, d=320, v_lo=100, v_hi=3000,
+                        top_k=300, top_p=0.8), coupling="gs")
+    _lockstep(wl.WORKLOADS["C4-topp"], max_steps=3, check_logits=False)
 
 
 def test_lockstep_scaled_video():
