@@ -257,7 +257,10 @@ __device__ __forceinline__ uint32_t select_regs(const float (&zv)[PER], const ui
 //   is taken exactly:  above(v) * 2^24 < P24 * S  with P24 = round(top_p * 2^24).
 //   Search: one histogram of masses over bins LINEAR in the logit (spreads a bell-shaped row
 //   over the bins), then radix levels over the key bits of the selected bin's members.
-// `each(f)` must call f(key, z) for every element of K1, the same elements on every call.
+// `each(f)` must call f(key, z) for every element of K1.  After the first level
+// `prepare(klo, khi)` is called once and then `near(f)` must call f for at least the elements of
+// K1 whose key lies in [klo, khi] (a path that can find them without reading the whole row again
+// does so; extra elements are filtered here).
 // mh: NBINS_P 64-bit bins (the space of the count histogram).  Uniform over the workgroup.
 constexpr int NBINS_P = NBINS / 2;
 static_assert(NBINS_P % THREADS == 0 || THREADS % NBINS_P == 0, "nucleus: bins per thread");
@@ -327,8 +330,8 @@ __device__ __forceinline__ uint32_t find_bin_mass(const unsigned long long* mh, 
   return bin;
 }
 
-template <class Each>
-__device__ __forceinline__ uint32_t nucleus_key(Each&& each, float m, float zmin, uint32_t p24,
+template <class Each, class Prepare, class Near>
+__device__ __forceinline__ uint32_t nucleus_key(Each&& each, Prepare&& prepare, Near&& near, float m, float zmin, uint32_t p24,
                                                 unsigned long long* mh, Small& sm) {
   const int tid = threadIdx.x;
   // logits more than 110 below the maximum weigh nothing: they all go to bin 0
@@ -348,6 +351,15 @@ __device__ __forceinline__ uint32_t nucleus_key(Each&& each, float m, float zmin
   __syncthreads();
   unsigned long long target = 0, above = 0;
   const int b1 = static_cast<int>(find_bin_mass<true>(mh, target, above, p24, sm));
+  // keys that can fall into bin b1: its interval of logits widened by a bin on either side
+  // (the rounding of lin_bin's arithmetic moves a logit by far less than a bin)
+  uint32_t near_lo = 0u, near_hi = 0xFFFFFFFFu;
+  if (scale > 0.f) {
+    const float inv = __fdiv_rn(m - zlo, static_cast<float>(NBINS_P - 1));
+    if (b1 > 1) near_lo = zkey(zlo + static_cast<float>(b1 - 1) * inv);
+    if (b1 < NBINS_P - 2) near_hi = zkey(zlo + static_cast<float>(b1 + 2) * inv);
+  }
+  prepare(near_lo, near_hi);
   // radix levels over the key bits of the members of bin b1
   uint32_t lo = 0;
   int s2 = 32;
@@ -356,7 +368,7 @@ __device__ __forceinline__ uint32_t nucleus_key(Each&& each, float m, float zmin
     s2 = width_bits > 11 ? width_bits - 11 : 0;
     zero();
     __syncthreads();
-    each([&](uint32_t key, float z) {
+    near([&](uint32_t key, float z) {
       if (lin_bin(z) == b1 && key >= lo &&
           (width_bits == 32 || (key - lo) >> width_bits == 0u))
         atomicAdd(&mh[(key - lo) >> s2], mass_of(z, m));
@@ -575,7 +587,8 @@ __device__ __forceinline__ bool finish_regs(const RowArgs& a, const RowRef& R, c
                                             const float (&zv)[PER], const float (&zq)[PER],
                                             const bool (&ok)[PER], bool filter, uint32_t cut_max,
                                             float zcx, float zpx, uint32_t* hist, uint32_t* cid,
-                                            float* cz, float* cq, int ccap, Small& sm, RowOut& out) {
+                                            float* cz, float* cq, int ccap, Small& sm, RowOut& out,
+                                            bool have_thr = false, float thr_given = 0.f) {
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int n = a.n;
   uint32_t kv[PER], kmax = 0, kmin = 0xFFFFFFFFu;
@@ -591,7 +604,7 @@ __device__ __forceinline__ bool finish_regs(const RowArgs& a, const RowRef& R, c
   if (filter) zero_hist(hist);            // published by the barrier inside block_minmax
   block_minmax(kmin, kmax, sm, false);
   const float m = key_to_float(kmax);
-  float thr = -INFINITY;
+  float thr = have_thr ? thr_given : -INFINITY;   // given: the caller has applied the filters
   if (filter) {
     // cid (ccap entries, all of them free until the compaction) takes the selected bin's members
     const uint32_t tkey = select_regs<PER>(zv, kv, ok, kmin, kmax, static_cast<uint32_t>(a.top_k), hist,
@@ -599,16 +612,16 @@ __device__ __forceinline__ bool finish_regs(const RowArgs& a, const RowRef& R, c
     if (tkey < cut_max) return false;     // an unseen logit could be >= the K-th candidate
     thr = key_to_float(tkey);
   }
-  if (TOPP && a.top_p24 != 0u) {          // nucleus filter on what top-k left
+  if (TOPP && a.top_p24 != 0u && !have_thr) {   // nucleus filter on what top-k left
     const float thr_k = thr;
     const float zmin = filter ? thr_k : (kmin <= kmax ? key_to_float(kmin) : m);
-    const uint32_t pkey = nucleus_key(
-        [&](auto&& f) {
+    auto each = [&](auto&& f) {
 #pragma unroll
-          for (int e = 0; e < PER; ++e)
-            if (ok[e] && zv[e] >= thr_k) f(kv[e], zv[e]);
-        },
-        m, zmin, a.top_p24, reinterpret_cast<unsigned long long*>(hist), sm);
+      for (int e = 0; e < PER; ++e)
+        if (ok[e] && zv[e] >= thr_k) f(kv[e], zv[e]);
+    };
+    const uint32_t pkey = nucleus_key(each, [](uint32_t, uint32_t) {}, each, m, zmin, a.top_p24,
+                                      reinterpret_cast<unsigned long long*>(hist), sm);
     thr = key_to_float(pkey);
   }
   // Kept ids are a random ~K/n of each thread's logits; compacting them into LDS (count /
@@ -856,16 +869,8 @@ __device__ __forceinline__ void full_path(const RowArgs& a, const RowRef& R, uns
   };
   uint32_t t16 = 0, need_ab = K;
   int ncand = 0, my_off = 0;
-  bool use_list = false;
-  if (filter) {
-    prefix_hist(false, 0u);
-    const uint32_t binA = find_bin(hist, need_ab, sm);
-    uint32_t low = 0;
-    if (sh > 0) {
-      prefix_hist(true, binA);
-      low = find_bin(hist, need_ab, sm);
-    }
-    t16 = p16min + (binA << sh) + low;
+  // ids whose 16-bit key prefix is >= t16: this thread's offset in a fixed order, and the total
+  auto count_candidates = [&]() {
     int my_cnt = 0;
     for (int c = tid; c < nchunks; c += THREADS) {
       const uint4 raw = *reinterpret_cast<const uint4*>(&k16[c << 3]);
@@ -877,10 +882,10 @@ __device__ __forceinline__ void full_path(const RowArgs& a, const RowRef& R, uns
       }
     }
     my_off = block_offsets(my_cnt, ncand, sm);
-    use_list = ncand <= kListCap;
-  }
-
-  if (use_list) {
+  };
+  // those ids (at most kListCap) as a list, their logits in registers, and the common tail;
+  // have_thr: the filters have been applied already and thr_given is their threshold
+  auto run_list = [&](bool have_thr, float thr_given) {
     int o = my_off;
     for (int c = tid; c < nchunks; c += THREADS) {
       const uint4 raw = *reinterpret_cast<const uint4*>(&k16[c << 3]);
@@ -908,13 +913,28 @@ __device__ __forceinline__ void full_path(const RowArgs& a, const RowRef& R, uns
     for (int e = 0; e < PER_LIST; ++e) zq[e] = 0.f;
     // the prefixes in LDS are spent: their space takes the compaction arrays
     const int ccap = min(kKeptCap, static_cast<int>(static_cast<size_t>(n8) * 2 / 12));
-    finish_regs<PER_LIST, false, GS, TOPP>(a, R, vid, zv, zq, ok, true, 0u, zcx, zpx, hist,
+    finish_regs<PER_LIST, false, GS, TOPP>(a, R, vid, zv, zq, ok, !have_thr, 0u, zcx, zpx, hist,
                           reinterpret_cast<uint32_t*>(smem), reinterpret_cast<float*>(smem) + ccap,
-                          reinterpret_cast<float*>(smem) + 2 * ccap, ccap, sm, out);
-    return;
+                          reinterpret_cast<float*>(smem) + 2 * ccap, ccap, sm, out, have_thr, thr_given);
+  };
+  if (filter) {
+    prefix_hist(false, 0u);
+    const uint32_t binA = find_bin(hist, need_ab, sm);
+    uint32_t low = 0;
+    if (sh > 0) {
+      prefix_hist(true, binA);
+      low = find_bin(hist, need_ab, sm);
+    }
+    t16 = p16min + (binA << sh) + low;
+    count_candidates();
+    if (ncand <= kListCap) {
+      run_list(false, 0.f);
+      return;
+    }
   }
 
   // in place: no filter, or the candidates do not fit (massive ties)
+  bool pfilter = filter;                 // candidates = ids whose 16-bit key prefix is >= t16
   auto for_each_candidate = [&](auto&& f) {
     for (int c = tid; c < nchunks; c += THREADS) {
       const uint4 raw = *reinterpret_cast<const uint4*>(&k16[c << 3]);
@@ -923,8 +943,40 @@ __device__ __forceinline__ void full_path(const RowArgs& a, const RowRef& R, uns
       for (int e = 0; e < 8; ++e) {
         const int v = (c << 3) + e;
         const uint32_t p = (w4[e >> 1] >> ((e & 1) * 16)) & 0xFFFFu;
-        if (v < n && (!filter || p >= t16)) f(v, p);
+        if (v < n && (!pfilter || p >= t16)) f(v, p);
       }
+    }
+  };
+  // The same candidates with their logits: f(v, z).  Without a filter every id is a candidate
+  // and the row is read in coalesced 32-byte pieces, two chunks per thread in flight; with one
+  // the few ids that pass the prefix test are gathered.
+  auto for_each_logit = [&](auto&& f) {
+    if (!pfilter && vec_ok) {
+      for (int c0 = tid; c0 < nchunks; c0 += 2 * THREADS) {
+        float zz[2][8];
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+          const int c = c0 + u * THREADS;
+          if (c < nchunks && (c << 3) + 7 < n) {
+            const float4 lo4 = *reinterpret_cast<const float4*>(zc + (c << 3));
+            const float4 hi4 = *reinterpret_cast<const float4*>(zc + (c << 3) + 4);
+            zz[u][0] = lo4.x; zz[u][1] = lo4.y; zz[u][2] = lo4.z; zz[u][3] = lo4.w;
+            zz[u][4] = hi4.x; zz[u][5] = hi4.y; zz[u][6] = hi4.z; zz[u][7] = hi4.w;
+          } else {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) zz[u][e] = (c < nchunks && (c << 3) + e < n) ? zc[(c << 3) + e] : 0.f;
+          }
+        }
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+          const int c = c0 + u * THREADS;
+#pragma unroll
+          for (int e = 0; e < 8; ++e)
+            if (c < nchunks && (c << 3) + e < n) f((c << 3) + e, zz[u][e]);
+        }
+      }
+    } else {
+      for_each_candidate([&](int v, uint32_t) { f(v, zc[v]); });
     }
   };
   float thr = -INFINITY;
@@ -949,20 +1001,61 @@ __device__ __forceinline__ void full_path(const RowArgs& a, const RowRef& R, uns
   if (TOPP && a.top_p24 != 0u) {          // nucleus filter on what top-k left
     const float thr_k = thr;
     const float zmin = filter ? thr_k : key_to_float(p16min << 16);
+    // members of the selected bin: ids found by the prefixes in LDS (appended in any order:
+    // the masses are integers), their logits gathered once and kept for the three radix levels
+    int near_cnt = 0;
+    bool near_dense = false;
+    float nz[PER_LIST];
     const uint32_t pkey = nucleus_key(
         [&](auto&& f) {
-          for_each_candidate([&](int v, uint32_t) {
-            const float z = zc[v];
+          for_each_logit([&](int, float z) {
             if (z >= thr_k) f(zkey(z), z);
           });
         },
+        [&](uint32_t klo, uint32_t khi) {
+          const uint32_t pa = klo >> 16, pb = khi >> 16;
+          if (tid == 0) sm.cursor = 0u;
+          __syncthreads();
+          for_each_candidate([&](int v, uint32_t p) {
+            if (p >= pa && p <= pb) {
+              const uint32_t slot = atomicAdd(&sm.cursor, 1u);
+              if (slot < static_cast<uint32_t>(kListCap)) list[slot] = static_cast<uint16_t>(v);
+            }
+          });
+          __syncthreads();
+          const uint32_t found = sm.cursor;
+          near_dense = found > static_cast<uint32_t>(kListCap);
+          near_cnt = near_dense ? 0 : static_cast<int>(found);
+#pragma unroll
+          for (int e = 0; e < PER_LIST; ++e) {
+            const int i = tid + e * THREADS;
+            nz[e] = i < near_cnt ? zc[list[i]] : 0.f;
+          }
+        },
+        [&](auto&& f) {
+          if (near_dense) {
+            for_each_logit([&](int, float z) {
+              if (z >= thr_k) f(zkey(z), z);
+            });
+          } else {
+#pragma unroll
+            for (int e = 0; e < PER_LIST; ++e)
+              if (tid + e * THREADS < near_cnt && nz[e] >= thr_k) f(zkey(nz[e]), nz[e]);
+          }
+        },
         m, zmin, a.top_p24, reinterpret_cast<unsigned long long*>(hist), sm);
     thr = key_to_float(pkey);
+    // the kept ids sit at or above the threshold's prefix: a short list takes the common tail
+    t16 = max(t16, pkey >> 16);
+    count_candidates();
+    if (ncand <= kListCap) {
+      run_list(true, thr);
+      return;
+    }
   }
   float sum = 0.f;
   int cnt = 0;
-  for_each_candidate([&](int v, uint32_t) {
-    const float z = zc[v];
+  for_each_logit([&](int, float z) {
     if (z >= thr) {
       sum += expf(z - m);
       ++cnt;
@@ -1008,15 +1101,15 @@ __device__ __forceinline__ void full_path(const RowArgs& a, const RowRef& R, uns
     const PRace pr = p_race_of_row(a, key, w3, j, R.it);
     out.prace = pr.on;
     if (pr.on) {
-      for_each_candidate([&](int v, uint32_t) {
-        const float pv = prob(zc[v], thr, lse_c);
+      for_each_logit([&](int v, float z) {
+        const float pv = prob(z, thr, lse_c);
         if (pv > 0.f) gumbel_entry(out, key, pr.w3s, j, pr.it, v, pv);
       });
     }
   }
   if (!out.accept) {
-    for_each_candidate([&](int v, uint32_t) {
-      const float pv = prob(zc[v], thr, lse_c);
+    for_each_logit([&](int v, float z) {
+      const float pv = prob(z, thr, lse_c);
       if (pv > 0.f) {
         const float qv = R.fresh ? q_uniform : prob(zp[v], R.thr_p, R.lse_p);
         const float rv = __fsub_rn(pv, qv);
