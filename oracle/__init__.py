@@ -11,5 +11,6 @@ Modules
   logits   LM head (fp64), CFG combine, id mask, temperature, top-k, softmax
   mrs      Modified Rejection Sampling (accept test + residual resample)
   gs       Gumbel-sharing coupling (shared-noise Gumbel-max draws)
+  diagnostics  per-position statistics: acceptance rate, collision probability, Renyi-2, Hamming
   scd      the SCD decode loop in its vectorised and its sequential form
 """

@@ -56,6 +56,7 @@ from . import philox
 from . import logits as lg
 from . import mrs as mrs_mod
 from . import gs as gs_mod
+from . import diagnostics as dg
 
 
 @dataclass
@@ -125,6 +126,7 @@ class ScdOracle:
         self.q = [dict() for _ in range(B)]   # pos -> fp64 row of the draft distribution
         self.out = np.full((B, N), -1, dtype=np.int64)
         self.accept_hist = [[] for _ in range(B)]
+        self.last_hamming = [(0, 0)] * B      # (changed drafts, surviving positions) of the last step
         self.positions_verified = 0
         for b in range(B):
             for j in range(min(L, N)):
@@ -219,6 +221,7 @@ class ScdOracle:
                     cfg.seed, b, j, t, philox.STREAM_RESID, cfg.n_allowed)
                 r = mrs_mod.mrs(p, q, x, u, U_fn, self.tol)
                 r["u"] = u
+                r["stats"] = dg.row_statistics(p, q)     # (beta, collision, sum p^2, sum q^2)
                 key = (b, j)
                 if accept_override and key in accept_override and accept_override[key] != r["k"]:
                     assert r["flag_accept"], "accept override on an unflagged draw"
@@ -276,6 +279,9 @@ class ScdOracle:
             a = min(first_rej + 1, Lw)
             for s in range(a):
                 self.out[b, i + s] = cfg.v_lo + res[b][s]["y"]
+            survivors = list(range(i + a, i + Lw))
+            self.last_hamming[b] = (dg.hamming(self.X[b, survivors],
+                                               [res[b][j - i]["next"] for j in survivors]), len(survivors))
             for s in range(a, Lw):                    # survivors: coupled redraft
                 j = i + s
                 self.X[b, j] = res[b][s]["next"]
