@@ -39,6 +39,9 @@ def parse():
     ap.add_argument("--warmup", type=int, default=0, help="untimed steps; 0 = one whole decode")
     ap.add_argument("--workload", default="C2",
                     help="C1 | C2 | C2-fullV | C3 | C4 (see paper_2510_24211_amd/workload.py)")
+    ap.add_argument("--diagnostics", action="store_true",
+                    help="also compute the per-position statistics in every step (config.diagnostics) "
+                         "and report their means over the recorded decode")
     ap.add_argument("--coupling", default="mc", choices=["mc", "gs"],
                     help="mc: maximal coupling (the paper's pi_MC, default); gs: Gumbel sharing (pi_GS)")
     ap.add_argument("--sjd-mix", type=float, default=0.0,
@@ -210,6 +213,7 @@ def measure(a, name, inputs):
     cfg = B.config_from_workload(w)
     cfg.coupling = B.COUPLING_GS if a.coupling == "gs" else B.COUPLING_MC
     cfg.sjd_mix = a.sjd_mix
+    cfg.diagnostics = int(a.diagnostics)
     s = B.Scd(cfg, dev)
     st = s.alloc_state()
     h = torch.empty((w.B, w.C, w.L, w.d), dtype=torch.bfloat16, device=dev)
@@ -229,6 +233,9 @@ def measure(a, name, inputs):
             chunks.append(torch.empty((CH, w.B, w.C, w.L, w.d), dtype=torch.bfloat16, device=dev))
         return chunks[i // CH][i % CH]
 
+    diag_sum = torch.zeros(4, dtype=torch.float64, device=dev)     # beta, C, bound, live rows
+    hamm_sum = torch.zeros(2, dtype=torch.int64, device=dev)       # changed drafts, survivors
+
     def record(limit):
         """Decode from a fresh state, at most `limit` steps; returns the iteration count."""
         s.reset(st)
@@ -238,6 +245,13 @@ def measure(a, name, inputs):
                 hi = h_of(i)
                 s.gather_hidden(table, w.age_cap, st, hi)
                 s.step(hi, W, st)
+                if a.diagnostics:                 # rows that are not live hold zeros
+                    d = s.state_field(st, B.F_DIAG).view(-1, 4).double()
+                    diag_sum[0] += d[:, 0].sum()
+                    diag_sum[1] += d[:, 1].sum()
+                    diag_sum[2] += (d[:, 2] * d[:, 3]).sqrt().sum()
+                    diag_sum[3] += (d[:, 2] > 0).sum()
+                    hamm_sum.add_(s.state_field(st, B.F_HAMM).view(-1, 2).sum(0))
                 i += 1
             rc, flags = s.status(st)
             assert rc == B.SCD_OK, (rc, flags)
@@ -357,7 +371,7 @@ def measure(a, name, inputs):
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": f"{w.name}: B={w.B} CFG={'on' if w.C == 2 else 'off'} L={w.L} "
-                               f"N={w.N} V={w.V} allowed={n} d={w.d} top_k={w.top_k} "
+                               f"N={w.N} V={w.V} allowed={n} d={w.d} top_k={w.top_k} top_p={w.top_p} "
                                f"lambda={w.cfg_lambda} seed={w.seed} coupling={a.coupling} sjd_mix={a.sjd_mix} "
                                f"(synthetic drift model)",
                    "decode_iterations": None if a.quick else int(nfe),
@@ -372,6 +386,14 @@ def measure(a, name, inputs):
                    "setup_s": t_setup},
         "roofline": roof,
     }
+    if a.diagnostics:       # means over the rows of the recorded decode (Sec. 3 of the paper)
+        ds, hs_ = diag_sum.cpu().numpy(), hamm_sum.cpu().numpy()
+        rows = max(ds[3], 1.0)
+        out["diagnostics"] = {"rows": int(ds[3]), "mean_acceptance_rate_1_minus_tv": ds[0] / rows,
+                              "mean_independent_collision_probability": ds[1] / rows,
+                              "mean_renyi2_collision_bound": ds[2] / rows,
+                              "changed_drafts": int(hs_[0]), "surviving_positions": int(hs_[1]),
+                              "hamming_fraction": float(hs_[0]) / max(float(hs_[1]), 1.0)}
     return out, w
 
 

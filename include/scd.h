@@ -84,6 +84,12 @@ typedef struct scd_config {
                           0 or 1 => off; must be in [0, 1]; needs v_hi - v_lo <= 65536.
                           Decided on 2^-40 fixed-point masses of expf(z - max), exactly:
                           mass above an id * 2^24 < round(top_p * 2^24) * total mass          */
+  int32_t diagnostics; /* 1 => every scd_step also writes the per-position statistics of the
+                          paper's analysis (Sec. 3: acceptance rate beta = 1 - D_TV(p, q),
+                          Prop. "SJD Collision Probability": C = sum_v p_v q_v and the two
+                          sums its Renyi-2 bound needs) to SCD_F_DIAG and the number of changed
+                          drafts (Hamming distance of consecutive drafts) to SCD_F_HAMM;
+                          0 => off; needs v_hi - v_lo <= 65536                               */
   uint64_t seed;
 } scd_config;
 
@@ -125,7 +131,18 @@ typedef enum scd_field {
   SCD_F_G = 17,       /* int32 [B, L]    last step's Gumbel-sharing / independent redraft draws,
                                          window order; -1 where the row drew none (written
                                          under SCD_COUPLING_GS or sjd_mix > 0 only)      */
-  SCD_F_COUNT = 18
+  SCD_F_DIAG = 18,    /* float [B, L, 4] last step, window order (diagnostics = 1 only):
+                                         [0] beta = sum_v min(p_v, q_v) = 1 - D_TV(p, q)
+                                         [1] C = sum_v p_v q_v
+                                         [2] sum_v p_v^2 = exp(-H_2(p))   [3] sum_v q_v^2
+                                         (C <= sqrt([2] * [3])); p = this iteration's
+                                         distribution of the position, q = the one its draft
+                                         came from (uniform for a first evaluation); rows that
+                                         are not live hold zeros                             */
+  SCD_F_S2 = 19,      /* float [2, B, L] internal: sum_v p_v^2 per parity and slot            */
+  SCD_F_HAMM = 20,    /* int32 [B, 2]    last step (diagnostics = 1 only): surviving window
+                                         positions whose draft changed, surviving positions   */
+  SCD_F_COUNT = 21
 } scd_field;
 
 /* Bytes of caller-provided device scratch a context needs; 0 on a bad config. */

@@ -17,7 +17,8 @@ SCD_OK, SCD_EINVAL, SCD_EWORKSPACE, SCD_EHIP, SCD_ENUMERIC, SCD_EUNSUPPORTED = 0
 
 # scd_field
 (F_POS, F_ITER, F_X, F_AGE, F_OUT, F_ACCEPT, F_Y, F_K, F_PX, F_QX, F_THR, F_LSE, F_NKEPT, F_Z,
- F_FLAGS, F_VERIFIED, F_TICKET, F_G) = range(18)
+ F_FLAGS, F_VERIFIED, F_TICKET, F_G, F_DIAG, F_S2, F_HAMM) = range(21)
+F_COUNT = 21
 COUPLING_MC, COUPLING_GS = 0, 1
 
 _FIELD_DTYPE = {
@@ -25,7 +26,8 @@ _FIELD_DTYPE = {
     F_OUT: torch.int32, F_ACCEPT: torch.int32, F_Y: torch.int32, F_K: torch.uint8,
     F_PX: torch.float32, F_QX: torch.float32, F_THR: torch.float32, F_LSE: torch.float32,
     F_NKEPT: torch.int32, F_Z: torch.float32, F_FLAGS: torch.int32, F_VERIFIED: torch.int32,
-    F_TICKET: torch.int32, F_G: torch.int32,
+    F_TICKET: torch.int32, F_G: torch.int32, F_DIAG: torch.float32, F_S2: torch.float32,
+    F_HAMM: torch.int32,
 }
 
 
@@ -35,7 +37,8 @@ class ScdConfig(ctypes.Structure):
                 ("v_hi", ctypes.c_int32), ("top_k", ctypes.c_int32),
                 ("temperature", ctypes.c_float), ("cfg_lambda", ctypes.c_float),
                 ("coupling", ctypes.c_int32), ("sjd_mix", ctypes.c_float),
-                ("top_p", ctypes.c_float), ("seed", ctypes.c_uint64)]
+                ("top_p", ctypes.c_float), ("diagnostics", ctypes.c_int32),
+                ("seed", ctypes.c_uint64)]
 
 
 class ScdError(RuntimeError):
@@ -94,9 +97,9 @@ def strerror(code):
 
 
 def make_config(B, L, N, V, d=0, v_lo=0, v_hi=-1, top_k=0, temperature=1.0, cfg_lambda=0.0,
-                seed=0, coupling=0, sjd_mix=0.0, top_p=0.0):
+                seed=0, coupling=0, sjd_mix=0.0, top_p=0.0, diagnostics=0):
     return ScdConfig(B, L, N, V, d, v_lo, V if v_hi < 0 else v_hi, top_k, temperature, cfg_lambda,
-                     coupling, sjd_mix, top_p, seed & 0xFFFFFFFFFFFFFFFF)
+                     coupling, sjd_mix, top_p, diagnostics, seed & 0xFFFFFFFFFFFFFFFF)
 
 
 def workspace_bytes(cfg):

@@ -73,6 +73,8 @@ struct Small {
   int first_rej;
   unsigned long long mtot[NW];   // nucleus: per-wavefront masses
   unsigned long long sel_mass;
+  float dred[3][NW];             // statistics: per-wavefront sums
+  int hamm;
 };
 
 // key with -0 folded onto +0, so that key order == float order for non-NaNs
@@ -387,6 +389,7 @@ struct RowRef {
   bool fresh, active;
   int x, b, s, p0, live, it;
   size_t widx, oidx;
+  size_t pidx;    // where the previous evaluation of the slot left its per-slot results (ring mode)
 };
 
 // pos, iter, mode, L, N repeat a.pos, a.iter, mode, L, N: the kernels receive them as plain
@@ -420,6 +423,7 @@ __device__ __forceinline__ RowRef locate_row(const RowArgs& a, int r, const int3
     const size_t sidx = static_cast<size_t>(R.b) * L + (R.p0 + R.s) % L;
     const size_t half = static_cast<size_t>(a.B) * L;
     R.oidx = par * half + sidx;
+    R.pidx = (par ^ 1) * half + sidx;
     R.x = a.x[sidx];
     R.fresh = a.age[sidx] == 0;
     R.zc = a.z_cur + static_cast<size_t>(par) * a.parity_stride + sidx * n;
@@ -524,6 +528,37 @@ __global__ __launch_bounds__(THREADS) void slice_kernel(const int32_t* const pos
   }
 }
 
+// Per-position statistics of the iteration (Sec. 3: acceptance rate beta = 1 - D_TV(p, q) =
+// sum_v min(p_v, q_v); Prop. "SJD Collision Probability": C = sum_v p_v q_v and its bound
+// sqrt(sum p^2 * sum q^2) = exp(-(H_2(p) + H_2(q)) / 2)).  d0..d2: this thread's share of
+// sum min(p, q), sum p q, sum p^2 over the kept ids.  sum q^2 is what the slot's previous
+// evaluation stored (1/n for a never-evaluated position).  Uniform over the workgroup.
+__device__ __forceinline__ void row_statistics_out(const RowArgs& a, const RowRef& R, float d0, float d1,
+                                                   float d2, float q_uniform, Small& sm) {
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  d0 = wave_sum(d0);
+  d1 = wave_sum(d1);
+  d2 = wave_sum(d2);
+  if (lane == 0) {
+    sm.dred[0][wave] = d0;
+    sm.dred[1][wave] = d1;
+    sm.dred[2][wave] = d2;
+  }
+  __syncthreads();
+  if (tid == 0) {
+    float s0 = 0.f, s1 = 0.f, s2 = 0.f;
+#pragma unroll
+    for (int w = 0; w < NW; ++w) {
+      s0 += sm.dred[0][w];
+      s1 += sm.dred[1][w];
+      s2 += sm.dred[2][w];
+    }
+    const float s2q = R.fresh ? q_uniform : a.s2[R.pidx];
+    *reinterpret_cast<float4*>(a.diag + R.widx * 4) = make_float4(s0, s1, s2, s2q);
+    a.s2[R.oidx] = s2;
+  }
+}
+
 // ---------------------------------------------------------------------------------
 // row kernel
 // ---------------------------------------------------------------------------------
@@ -582,7 +617,7 @@ __device__ __forceinline__ PRace p_race_of_row(const RowArgs& a, uint2 key, uint
 // Otherwise (ids scattered over the row) the previous logits of the KEPT ids are gathered
 // here, right after the compaction, so that the round trip hides behind the normaliser and
 // the accept draw.  The LDS arrays cid / cz / cq hold ccap entries each.
-template <int PER, bool PREQ, bool GS, bool TOPP>
+template <int PER, bool PREQ, bool GS, bool EXTRA>
 __device__ __forceinline__ bool finish_regs(const RowArgs& a, const RowRef& R, const int (&vid)[PER],
                                             const float (&zv)[PER], const float (&zq)[PER],
                                             const bool (&ok)[PER], bool filter, uint32_t cut_max,
@@ -612,7 +647,7 @@ __device__ __forceinline__ bool finish_regs(const RowArgs& a, const RowRef& R, c
     if (tkey < cut_max) return false;     // an unseen logit could be >= the K-th candidate
     thr = key_to_float(tkey);
   }
-  if (TOPP && a.top_p24 != 0u && !have_thr) {   // nucleus filter on what top-k left
+  if (EXTRA && a.top_p24 != 0u && !have_thr) {   // nucleus filter on what top-k left
     const float thr_k = thr;
     const float zmin = filter ? thr_k : (kmin <= kmax ? key_to_float(kmin) : m);
     auto each = [&](auto&& f) {
@@ -704,6 +739,26 @@ __device__ __forceinline__ bool finish_regs(const RowArgs& a, const RowRef& R, c
   out.best_id = 0x7FFFFFFF;
   out.gbest = INFINITY;
   out.gbest_id = 0x7FFFFFFF;
+  if (EXTRA && a.diag != nullptr && a.mode == kRowRing) {
+    float d0 = 0.f, d1 = 0.f, d2 = 0.f;
+    auto add = [&](float zc_v, float zq_v) {
+      const float pv = expf(zc_v - lse_c);
+      const float qv = R.fresh ? q_uniform : prob(zq_v, R.thr_p, R.lse_p);
+      d0 += fminf(pv, qv);
+      d1 += pv * qv;
+      d2 += pv * pv;
+    };
+    if (compact) {
+#pragma unroll
+      for (int q = 0; q < KPT; ++q)
+        if (rid[q] >= 0) add(rz[q], rq[q]);
+    } else {
+#pragma unroll
+      for (int e = 0; e < PER; ++e)
+        if (kept[e]) add(zv[e], PREQ ? zq[e] : (want_q ? R.zp[vid[e]] : 0.f));
+    }
+    row_statistics_out(a, R, d0, d1, d2, q_uniform, sm);
+  }
   if (GS) {                        // next draft should the row survive
     const PRace pr = p_race_of_row(a, key, w3, j, R.it);
     out.prace = pr.on;
@@ -783,7 +838,7 @@ __device__ __forceinline__ bool finish_regs(const RowArgs& a, const RowRef& R, c
 // The complete in-place path: one coalesced read of the row, 16-bit key prefixes in
 // LDS, histogram select; then a candidate list in registers, or in-place scans when
 // top-k is off or the candidates do not fit.
-template <bool GS, bool TOPP>
+template <bool GS, bool EXTRA>
 __device__ __forceinline__ void full_path(const RowArgs& a, const RowRef& R, unsigned char* smem,
                                           float zcx, float zpx, Small& sm, RowOut& out) {
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -913,7 +968,7 @@ __device__ __forceinline__ void full_path(const RowArgs& a, const RowRef& R, uns
     for (int e = 0; e < PER_LIST; ++e) zq[e] = 0.f;
     // the prefixes in LDS are spent: their space takes the compaction arrays
     const int ccap = min(kKeptCap, static_cast<int>(static_cast<size_t>(n8) * 2 / 12));
-    finish_regs<PER_LIST, false, GS, TOPP>(a, R, vid, zv, zq, ok, !have_thr, 0u, zcx, zpx, hist,
+    finish_regs<PER_LIST, false, GS, EXTRA>(a, R, vid, zv, zq, ok, !have_thr, 0u, zcx, zpx, hist,
                           reinterpret_cast<uint32_t*>(smem), reinterpret_cast<float*>(smem) + ccap,
                           reinterpret_cast<float*>(smem) + 2 * ccap, ccap, sm, out, have_thr, thr_given);
   };
@@ -998,7 +1053,7 @@ __device__ __forceinline__ void full_path(const RowArgs& a, const RowRef& R, uns
     }
     thr = key_to_float((t16 << 16) | lowkey);
   }
-  if (TOPP && a.top_p24 != 0u) {          // nucleus filter on what top-k left
+  if (EXTRA && a.top_p24 != 0u) {          // nucleus filter on what top-k left
     const float thr_k = thr;
     const float zmin = filter ? thr_k : key_to_float(p16min << 16);
     // members of the selected bin: ids found by the prefixes in LDS (appended in any order:
@@ -1097,6 +1152,19 @@ __device__ __forceinline__ void full_path(const RowArgs& a, const RowRef& R, uns
   out.best_id = 0x7FFFFFFF;
   out.gbest = INFINITY;
   out.gbest_id = 0x7FFFFFFF;
+  if (EXTRA && a.diag != nullptr && a.mode == kRowRing) {
+    float d0 = 0.f, d1 = 0.f, d2 = 0.f;
+    for_each_logit([&](int v, float z) {
+      const float pv = prob(z, thr, lse_c);
+      if (pv > 0.f) {
+        const float qv = R.fresh ? q_uniform : prob(zp[v], R.thr_p, R.lse_p);
+        d0 += fminf(pv, qv);
+        d1 += pv * qv;
+        d2 += pv * pv;
+      }
+    });
+    row_statistics_out(a, R, d0, d1, d2, q_uniform, sm);
+  }
   if (GS) {
     const PRace pr = p_race_of_row(a, key, w3, j, R.it);
     out.prace = pr.on;
@@ -1129,7 +1197,7 @@ __device__ __forceinline__ void full_path(const RowArgs& a, const RowRef& R, uns
 }
 
 // The whole row in registers, PER logits per thread (n <= PER * THREADS).
-template <int PER, bool GS, bool TOPP>
+template <int PER, bool GS, bool EXTRA>
 __device__ __forceinline__ void direct_path(const RowArgs& a, const RowRef& R, unsigned char* smem,
                                             bool filter, float zcx, float zpx, Small& sm, RowOut& out) {
   const int tid = threadIdx.x, n = a.n;
@@ -1162,14 +1230,15 @@ __device__ __forceinline__ void direct_path(const RowArgs& a, const RowRef& R, u
     }
   }
   uint32_t* cid = hist + NBINS;
-  finish_regs<PER, true, GS, TOPP>(a, R, vid, zv, zq, ok, filter, 0u, zcx, zpx, hist, cid,
+  finish_regs<PER, true, GS, EXTRA>(a, R, vid, zv, zq, ok, filter, 0u, zcx, zpx, hist, cid,
                    reinterpret_cast<float*>(cid + kKeptCap),
                    reinterpret_cast<float*>(cid + 2 * kKeptCap), kKeptCap, sm, out);
 }
 
-// GS: the row also makes a Gumbel-max draw from p; TOPP: the nucleus filter is compiled in
-// (kept out of the other instances: its live ranges cost the hot kernels registers)
-template <bool GS, bool TOPP>
+// GS: the row also makes a Gumbel-max draw from p; EXTRA: the optional parts are compiled in
+// (nucleus filter, per-position statistics; kept out of the other instances: their live ranges
+// cost the hot kernels registers)
+template <bool GS, bool EXTRA>
 __global__ __launch_bounds__(THREADS) void row_kernel(const int32_t* const pos_, const int32_t* const iter_,
                                                       const int mode_, const int L_, const int N_,
                                                       const int P, const int capE, const RowArgs a) {
@@ -1187,6 +1256,13 @@ __global__ __launch_bounds__(THREADS) void row_kernel(const int32_t* const pos_,
       if (a.px) a.px[R.widx] = 0.f;
       if (a.qx) a.qx[R.widx] = 0.f;
       if (a.mode == kRowRing && R.s == 0) a.accept_len[R.b] = 0;   // finished sequence
+      if (EXTRA && a.diag != nullptr && a.mode == kRowRing) {
+        *reinterpret_cast<float4*>(a.diag + R.widx * 4) = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (R.s == 0) {
+          a.hamm[2 * R.b] = 0;
+          a.hamm[2 * R.b + 1] = 0;
+        }
+      }
     }
     return;
   }
@@ -1201,8 +1277,8 @@ __global__ __launch_bounds__(THREADS) void row_kernel(const int32_t* const pos_,
   bool done = false;
   if (n <= kDirectMaxN) {
     // ---- the whole row in registers ------------------------------------------------
-    if (n <= kDirectMaxN / 2) direct_path<PER_DIRECT / 2, GS, TOPP>(a, R, smem, filter, zcx, zpx, sm, out);
-    else direct_path<PER_DIRECT, GS, TOPP>(a, R, smem, filter, zcx, zpx, sm, out);
+    if (n <= kDirectMaxN / 2) direct_path<PER_DIRECT / 2, GS, EXTRA>(a, R, smem, filter, zcx, zpx, sm, out);
+    else direct_path<PER_DIRECT, GS, EXTRA>(a, R, smem, filter, zcx, zpx, sm, out);
     done = true;
   } else if (filter && a.cand && P > 0) {
     // ---- candidates emitted by the slice kernel ----------------------------------
@@ -1248,12 +1324,12 @@ __global__ __launch_bounds__(THREADS) void row_kernel(const int32_t* const pos_,
 #pragma unroll
       for (int e = 0; e < PER_LIST; ++e) zq[e] = 0.f;
       const int ccap = min(kKeptCap, static_cast<int>(static_cast<size_t>((n + 7) & ~7) * 2 / 12));
-      done = finish_regs<PER_LIST, false, GS, TOPP>(a, R, vid, zv, zq, ok, true, cut_max, zcx, zpx, hist,
+      done = finish_regs<PER_LIST, false, GS, EXTRA>(a, R, vid, zv, zq, ok, true, cut_max, zcx, zpx, hist,
                                    reinterpret_cast<uint32_t*>(smem), reinterpret_cast<float*>(smem) + ccap,
                                    reinterpret_cast<float*>(smem) + 2 * ccap, ccap, sm, out);
     }
   }
-  if (!done) full_path<GS, TOPP>(a, R, smem, zcx, zpx, sm, out);
+  if (!done) full_path<GS, EXTRA>(a, R, smem, zcx, zpx, sm, out);
   if (a.mode == kRowSelectOnly) return;
 
   // ---- winner of the race (lexicographic (score, id) minimum) -------------------
@@ -1330,6 +1406,7 @@ __global__ __launch_bounds__(THREADS) void row_kernel(const int32_t* const pos_,
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
     sm.last = __hip_atomic_fetch_add(&a.ticket[b], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == live - 1;
     sm.first_rej = live;
+    sm.hamm = 0;
   }
   __syncthreads();
   if (!sm.last) return;
@@ -1351,7 +1428,9 @@ __global__ __launch_bounds__(THREADS) void row_kernel(const int32_t* const pos_,
     if (tid >= acc) {
       // survivors: the MRS output is the coupled redraft (pi_MC); under pi_GS, or when the
       // alpha-coupling switch chose the independent redraft, it is the row's Gumbel-max draw
-      a.X[sidx] = (GS && gg >= 0) ? gg : yy;
+      const int next = (GS && gg >= 0) ? gg : yy;
+      if (EXTRA && a.diag != nullptr && next != a.X[sidx]) atomicAdd(&sm.hamm, 1);
+      a.X[sidx] = next;
       a.age_w[sidx] += 1;
     } else {
       const int np = p0 + a.L + tid;
@@ -1365,6 +1444,13 @@ __global__ __launch_bounds__(THREADS) void row_kernel(const int32_t* const pos_,
     a.iter[b] = R.it + 1;
     a.verified[b] += live;
     a.ticket[b] = 0;
+  }
+  if (EXTRA && a.diag != nullptr) {     // drafts that changed among the surviving positions
+    __syncthreads();
+    if (tid == 0) {
+      a.hamm[2 * b] = sm.hamm;
+      a.hamm[2 * b + 1] = live - acc;
+    }
   }
 }
 
@@ -1417,7 +1503,7 @@ hipError_t launch_row(const RowArgs& a_in, hipStream_t s) {
     configured = lds;
   }
   const bool gs = (a.gumbel || a.alpha < 1.0f) && a.g && a.mode != kRowSelectOnly;
-  const bool topp = a.top_p24 != 0u;
+  const bool topp = a.top_p24 != 0u || a.diag != nullptr;   // the instances with the optional parts
   auto* const kernel = gs ? (topp ? row_kernel<true, true> : row_kernel<true, false>)
                           : (topp ? row_kernel<false, true> : row_kernel<false, false>);
   hipLaunchKernelGGL(kernel, dim3(a.rows), dim3(THREADS), lds, s, a.pos, a.iter, a.mode, a.L, a.N, P, capE, a);

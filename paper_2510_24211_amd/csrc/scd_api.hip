@@ -34,6 +34,7 @@ bool valid_config(const scd_config* c) {
   if (!(c->sjd_mix >= 0.f && c->sjd_mix <= 1.f)) return false;
   if (c->coupling < 0) return false;
   if (!(c->top_p >= 0.f && c->top_p <= 1.f)) return false;
+  if (c->diagnostics != 0 && c->diagnostics != 1) return false;
   return true;
 }
 
@@ -66,6 +67,9 @@ Layout make_layout(const scd_config& c) {
   sz[SCD_F_VERIFIED] = 4 * B;
   sz[SCD_F_TICKET] = 4 * B;
   sz[SCD_F_G] = 4 * B * L;
+  sz[SCD_F_DIAG] = 4 * 4 * B * L;
+  sz[SCD_F_S2] = 4 * 2 * B * L;
+  sz[SCD_F_HAMM] = 4 * 2 * B;
   Layout lay;
   size_t o = 0;
   for (int f = 0; f < SCD_F_COUNT; ++f) {
@@ -146,6 +150,11 @@ int run_tail(scd_ctx* c, void* st) {
     ra.gumbel = c->cfg.coupling == SCD_COUPLING_GS;
     ra.alpha = 1.0f - c->cfg.sjd_mix;
     ra.g = field<int32_t>(c, st, SCD_F_G);
+    if (c->cfg.diagnostics) {
+      ra.diag = field<float>(c, st, SCD_F_DIAG);
+      ra.s2 = field<float>(c, st, SCD_F_S2);
+      ra.hamm = field<int32_t>(c, st, SCD_F_HAMM);
+    }
     return hip_rc(scd::launch_row(ra, c->stream));
   }
   // rows too long for the LDS-resident kernel: select -> MRS -> commit
@@ -213,6 +222,7 @@ int scd_create(scd_ctx** out, const scd_config* cfg, void* d_workspace, size_t w
   if (cfg->coupling != SCD_COUPLING_MC && cfg->coupling != SCD_COUPLING_GS) return SCD_EUNSUPPORTED;
   // the Gumbel draw lives in the fused row kernel only
   if (top_p24_of(*cfg) != 0u && cfg->v_hi - cfg->v_lo > scd::kRowKernelMaxN) return SCD_EUNSUPPORTED;
+  if (cfg->diagnostics && cfg->v_hi - cfg->v_lo > scd::kRowKernelMaxN) return SCD_EUNSUPPORTED;
   if ((cfg->coupling == SCD_COUPLING_GS || cfg->sjd_mix > 0.f) &&
       cfg->v_hi - cfg->v_lo > scd::kRowKernelMaxN)
     return SCD_EUNSUPPORTED;

@@ -105,6 +105,10 @@ struct RowArgs {
   int B, L, N, n, top_k, v_lo;
   // nucleus filter: round(top_p * 2^24), 0 => off.  Applied to what top-k left.
   uint32_t top_p24;
+  // per-position statistics (ring mode only; all three null => off)
+  float* diag;           // [B, L, 4] window order: sum min(p,q), sum p q, sum p^2, sum q^2
+  float* s2;             // [2, B, L] sum p^2 per parity and slot
+  int32_t* hamm;         // [B, 2]    changed drafts, surviving positions
   uint64_t seed;
   // scratch for the slice kernel (rows longer than 8192 ids): row_candidate_bytes(rows)
   // bytes of device memory, 256-byte aligned, or null (then rows are processed whole)

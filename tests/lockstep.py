@@ -28,7 +28,8 @@ def bf16_tensor(bits_np, device):
 
 
 class LockStep:
-    def __init__(self, w: wl.Workload, device="cuda:0", check_logits=True, coupling="mc", sjd_mix=0.0):
+    def __init__(self, w: wl.Workload, device="cuda:0", check_logits=True, coupling="mc", sjd_mix=0.0,
+                 diagnostics=False):
         self.w = w
         self.device = device
         self.check_logits = check_logits
@@ -36,6 +37,8 @@ class LockStep:
         self.cfg_c = B.config_from_workload(w)
         self.cfg_c.coupling = B.COUPLING_GS if coupling == "gs" else B.COUPLING_MC
         self.cfg_c.sjd_mix = sjd_mix
+        self.cfg_c.diagnostics = int(diagnostics)
+        self.diagnostics = diagnostics
         # the library's alpha is fl32(1 - sjd_mix); the oracle gets exactly that number
         alpha = float(np.float32(1.0) - np.float32(self.cfg_c.sjd_mix))
         self.has_g = coupling == "gs" or sjd_mix > 0
@@ -63,7 +66,7 @@ class LockStep:
             ("pos", B.F_POS), ("iter", B.F_ITER), ("X", B.F_X), ("age", B.F_AGE), ("out", B.F_OUT),
             ("acc", B.F_ACCEPT), ("y", B.F_Y), ("k", B.F_K), ("px", B.F_PX), ("qx", B.F_QX),
             ("thr", B.F_THR), ("lse", B.F_LSE), ("nkept", B.F_NKEPT), ("z", B.F_Z),
-            ("verified", B.F_VERIFIED), ("g", B.F_G)]}
+            ("verified", B.F_VERIFIED), ("g", B.F_G), ("diag", B.F_DIAG), ("hamm", B.F_HAMM)]}
         self.stats = dict(steps=0, draws=0, flag_accept=0, flag_resid=0, flag_topk=0, flag_gs=0,
                           adopt_accept=0, adopt_resid=0, adopt_topk=0, adopt_gs=0,
                           max_logit_abs=0.0, max_logit_rel=0.0, max_lse_abs=0.0, max_prob_rel=0.0)
@@ -118,7 +121,8 @@ class LockStep:
 
         # ---- download what the step produced --------------------------------
         g = {k: v[k].cpu().numpy() for k in ("pos", "iter", "X", "age", "acc", "y", "k", "px",
-                                             "qx", "thr", "lse", "nkept", "verified", "g")}
+                                             "qx", "thr", "lse", "nkept", "verified", "g", "diag",
+                                             "hamm")}
         g["thr"] = g["thr"].reshape(2, Bn, L)
         g["lse"] = g["lse"].reshape(2, Bn, L)
         g["nkept"] = g["nkept"].reshape(2, Bn, L)
@@ -231,8 +235,32 @@ class LockStep:
                     if self.has_g:
                         assert int(gg[b, s]) == -1
 
+        # ---- per-position statistics ---------------------------------------
+        if self.diagnostics:
+            gd = g["diag"].reshape(Bn, L, 4)
+            for b in range(Bn):
+                for s in range(L):
+                    if s >= lives[b]:
+                        assert not gd[b, s].any()
+                        continue
+                    if (b, i_b[b] + s) in keep_override:
+                        continue
+                    for got, want in zip(gd[b, s], res[b][s]["stats"]):
+                        err = abs(float(got) - want)
+                        st["max_stat_rel"] = max(st.get("max_stat_rel", 0.0), err / max(want, 1e-30))
+                        assert err <= 4 * self.prob_rtol * want + 1e-9, \
+                            f"statistic differs b={b} s={s}: gpu {gd[b, s]} oracle {res[b][s]['stats']}"
+
         # ---- commit --------------------------------------------------------
         acc = o.commit(plan, res)
+        if self.diagnostics:
+            gh = g["hamm"].reshape(Bn, 2)
+            for b in range(Bn):
+                if lives[b]:
+                    assert tuple(int(x) for x in gh[b]) == o.last_hamming[b], \
+                        f"changed drafts differ: gpu {gh[b]} oracle {o.last_hamming[b]}"
+                else:
+                    assert not gh[b].any()
         assert list(g["acc"]) == acc, f"accept lengths differ: {list(g['acc'])} vs {acc}"
         assert list(g["pos"]) == list(o.i) and list(g["iter"]) == list(o.t)
         assert int(g["verified"].sum()) == o.positions_verified

@@ -81,6 +81,8 @@ def test_create_rejects_bad_arguments_without_touching_the_device():
     assert lib.scd_create(ctypes.byref(ctx), ctypes.byref(big), fake, 1 << 40, None) == B.SCD_EUNSUPPORTED
     wide = B.make_config(B=1, L=8, N=64, V=70000, top_p=0.8)          # nucleus: rows <= 65536 ids
     assert lib.scd_create(ctypes.byref(ctx), ctypes.byref(wide), fake, 1 << 40, None) == B.SCD_EUNSUPPORTED
+    dg = B.make_config(B=1, L=8, N=64, V=70000, diagnostics=1)        # statistics: rows <= 65536 ids
+    assert lib.scd_create(ctypes.byref(ctx), ctypes.byref(dg), fake, 1 << 40, None) == B.SCD_EUNSUPPORTED
     off = B.make_config(B=1, L=8, N=64, V=1024, top_p=1.25)            # mass outside [0, 1]
     assert lib.scd_create(ctypes.byref(ctx), ctypes.byref(off), fake, need, None) == B.SCD_EINVAL
     assert lib.scd_create(ctypes.byref(ctx), ctypes.byref(cfg), fake, need, None) == B.SCD_OK
@@ -97,7 +99,7 @@ def test_create_rejects_bad_arguments_without_touching_the_device():
     total = B.state_bytes(cfg)
     base = 0x100000
     spans = []
-    for f in range(18):
+    for f in range(B.F_COUNT):
         p, nb = ctypes.c_void_p(), ctypes.c_size_t()
         assert lib.scd_state_field(ctx, ctypes.c_void_p(base), f, ctypes.byref(p), ctypes.byref(nb)) == 0
         assert p.value % 256 == 0 and nb.value > 0
@@ -105,7 +107,7 @@ def test_create_rejects_bad_arguments_without_touching_the_device():
     spans.sort()
     assert spans[-1][1] <= total
     assert all(a[1] <= b[0] for a, b in zip(spans, spans[1:]))
-    assert lib.scd_state_field(ctx, ctypes.c_void_p(base), 18, ctypes.byref(p), ctypes.byref(nb)) == B.SCD_EINVAL
+    assert lib.scd_state_field(ctx, ctypes.c_void_p(base), B.F_COUNT, ctypes.byref(p), ctypes.byref(nb)) == B.SCD_EINVAL
     assert lib.scd_destroy(ctx) == B.SCD_OK
     assert lib.scd_destroy(None) == B.SCD_EINVAL
     assert B.strerror(B.SCD_EWORKSPACE).startswith("workspace")

@@ -285,6 +285,25 @@ def test_lockstep_nucleus_scaled_and_video_prefix():
     _lockstep(wl.WORKLOADS["C4-topp"], max_steps=3, check_logits=False)
 
 
+@pytest.mark.parametrize("kw,opts", [
+    (dict(N=64, L=8, seed=0), dict()),                                     # 8 logits per thread
+    (dict(N=70, L=8, seed=36, B=3, V=1000, top_k=100), dict(coupling="gs")),   # batch, ragged n, pi_GS
+    (dict(N=40, L=8, seed=37, V=12000, top_k=300, age_cap=4), dict(sjd_mix=0.5)),   # 16 per thread, alpha = 0.5
+    (dict(N=16, L=4, seed=38, V=20000, age_cap=4), dict()),                # in-place path
+    (dict(N=16, L=4, seed=39, V=40000, top_k=2000, age_cap=4), dict()),    # slice kernel + candidates
+    (dict(N=40, L=8, seed=40, V=3000, top_p=0.8), dict()),                 # with the nucleus filter
+])
+def test_lockstep_statistics_toy_variants(kw, opts):
+    ls, st = _lockstep(wl.scaled(wl.WORKLOADS["C0"], name="toy", **kw), diagnostics=True, **opts)
+    assert st["max_stat_rel"] < 2e-5
+
+
+def test_lockstep_statistics_scaled_and_C2_prefix():
+    _lockstep(wl.scaled(wl.WORKLOADS["C3"], name="C3s", B=4, N=80, V=4096, d=256, v_lo=4, v_hi=1028,
+                        top_k=250), diagnostics=True)
+    _lockstep(wl.WORKLOADS["C2"], max_steps=10, check_logits=False, diagnostics=True)
+
+
 def test_lockstep_scaled_video():
     _lockstep(wl.scaled(wl.WORKLOADS["C4"], name="C4s", N=8 * 24, V=2000, d=512, top_k=300, L=64))
 
