@@ -109,7 +109,8 @@ def _select_case(z, top_k, top_p=0.0):
 
 @pytest.mark.parametrize("n,top_k", [(1024, 0), (1024, 100), (1000, 1), (1000, 999), (1000, 1000),
                                      (1000, 5000), (8192, 2000), (65536, 2000), (16384, 1000),
-                                     (64000, 2000), (5, 2), (1, 1), (4097, 33)])
+                                     (64000, 2000), (5, 2), (1, 1), (4097, 33),
+                                     (40000, 3500), (65536, 10000), (20000, 19999), (30001, 7)])
 def test_select_softmax_against_oracle(n, top_k):
     g = np.random.default_rng(n * 31 + top_k)
     z = (g.standard_normal((6, n)) * 3).astype(np.float32)
@@ -124,7 +125,8 @@ def test_select_softmax_against_oracle(n, top_k):
 @pytest.mark.parametrize("n,top_k,top_p", [(1024, 0, 0.8), (1000, 100, 0.8), (1000, 0, 0.02), (1000, 0, 0.9999),
                                            (8192, 2000, 0.8), (16384, 0, 0.8), (12000, 3000, 0.95),
                                            (64000, 0, 0.8), (65536, 2000, 0.5), (40000, 0, 0.3),
-                                           (5, 0, 0.7), (2, 0, 0.5), (1, 0, 0.8), (4097, 33, 0.6)])
+                                           (5, 0, 0.7), (2, 0, 0.5), (1, 0, 0.8), (4097, 33, 0.6),
+                                           (40000, 5000, 0.9), (65536, 12000, 0.97), (30001, 0, 0.6)])
 def test_select_nucleus_against_oracle(n, top_k, top_p):
     g = np.random.default_rng(n * 37 + top_k)
     z = (g.standard_normal((7, n)) * 3).astype(np.float32)
