@@ -43,6 +43,17 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 // which keeps arrays of it in scratch memory)
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
+// One 16-byte piece of W.  NT: non-temporal load -- the line is not kept in the caches it
+// passes.  A slice of W that cannot stay in the 256 MB memory-side cache until the next step
+// only evicts what could (the hidden rows in L2, the logits): streaming it past the caches
+// took the full-vocabulary LM head from 96 to 87 us.  A slice that fits (C2: 67 MB) is served
+// from that cache step after step and loses 3 us when loaded this way.
+template <bool NT>
+__device__ __forceinline__ u32x4 load_w(const u32x4* p) {
+  if constexpr (NT) return __builtin_nontemporal_load(p);
+  else return *p;
+}
+
 constexpr int BK = 64;          // k elements per W tile (128 bytes per row)
 constexpr int PITCH = BK + 8;   // LDS row pitch in bf16 elements (144 bytes)
 
@@ -148,7 +159,7 @@ __device__ __forceinline__ void epilogue(const LmHeadArgs& a, const f32x16 (&acc
   }
 }
 
-template <int RBW, int C, int NWV>
+template <int RBW, int C, int NWV, bool NT>
 __global__ __launch_bounds__((Cfg<RBW, C, NWV>::THREADS)) void lm_head_kernel(
     const LmHeadArgs a, const int nLb, const int nRB, const int VT, const int MT, const RowMap rm) {
   using K = Cfg<RBW, C, NWV>;
@@ -214,7 +225,7 @@ __global__ __launch_bounds__((Cfg<RBW, C, NWV>::THREADS)) void lm_head_kernel(
     const int kt = ktile(t, valid);
     const uint32_t kb = min(static_cast<uint32_t>(kt * BK + chunk * 8) * 2u, kclamp);
 #pragma unroll
-    for (int i = 0; i < 4; ++i) wreg[slot][i] = *reinterpret_cast<const u32x4*>(Wb + (woff[i] + kb));
+    for (int i = 0; i < 4; ++i) wreg[slot][i] = load_w<NT>(reinterpret_cast<const u32x4*>(Wb + (woff[i] + kb)));
   };
   auto wstore = [&](int slot) {
 #pragma unroll
@@ -381,7 +392,7 @@ struct Gemm8Cfg {
   static constexpr int LDS_BYTES = 2 * (W_LDS + H_LDS) * 2;
 };
 
-template <int C>
+template <int C, bool NT>
 __global__ __launch_bounds__(512) void lm_head_gemm8_kernel(const LmHeadArgs a, const int nLb,
                                                             const int nRB, const int VT) {
   using K = Gemm8Cfg<C>;
@@ -425,7 +436,7 @@ __global__ __launch_bounds__(512) void lm_head_gemm8_kernel(const LmHeadArgs a, 
     kok[stage] = t < KT && k < d;                      // a tile past the end counts as zeros
     const uint32_t kb = min(static_cast<uint32_t>(k) * 2u, kclamp);
 #pragma unroll
-    for (int i = 0; i < WL; ++i) wreg[stage][i] = *reinterpret_cast<const u32x4*>(Wb + (woff[i] + kb));
+    for (int i = 0; i < WL; ++i) wreg[stage][i] = load_w<NT>(reinterpret_cast<const u32x4*>(Wb + (woff[i] + kb)));
 #pragma unroll
     for (int i = 0; i < HL; ++i) hreg[stage][i] = *reinterpret_cast<const u32x4*>(Hb + (hoff[i] + kb));
   };
@@ -586,7 +597,7 @@ __global__ __launch_bounds__((SplitCfg<RBW, C, KS>::THREADS)) void lm_head_split
     const int kt = ktile(t, valid);
     const uint32_t kb = min(static_cast<uint32_t>(kt * BK + chunk * 8) * 2u, kclamp);
 #pragma unroll
-    for (int i = 0; i < 4; ++i) wreg[slot][i] = *reinterpret_cast<const u32x4*>(Wb + (woff[i] + kb));
+    for (int i = 0; i < 4; ++i) wreg[slot][i] = load_w<false>(reinterpret_cast<const u32x4*>(Wb + (woff[i] + kb)));
   };
   auto hload = [&](int slot, int t) {
     bool valid;
@@ -698,6 +709,9 @@ RowMap make_row_map(const LmHeadArgs& a, int BN, int VT, bool affine, int* tiles
   return m;
 }
 
+// W is streamed past the caches when its slice cannot stay in the memory-side cache anyway
+bool stream_w(const LmHeadArgs& a) { return 2.0 * a.d * a.n > 192.0 * 1024 * 1024; }
+
 template <int RBW, int C, int NWV>
 hipError_t launch_wide(const LmHeadArgs& a, hipStream_t s) {
   using K = Cfg<RBW, C, NWV>;
@@ -710,8 +724,12 @@ hipError_t launch_wide(const LmHeadArgs& a, hipStream_t s) {
   // in one residue class its requests would pile onto one channel at a time (measured: 124 us
   // against 94 us for the full vocabulary), so rows stay consecutive here.
   const RowMap rm = make_row_map(a, K::BN, VT, false, &JT);
-  hipLaunchKernelGGL((lm_head_kernel<RBW, C, NWV>), dim3(JT * 8 * MT), dim3(K::THREADS), 0, s, a, nLb,
-                     nRB, VT, MT, rm);
+  if (stream_w(a))
+    hipLaunchKernelGGL((lm_head_kernel<RBW, C, NWV, true>), dim3(JT * 8 * MT), dim3(K::THREADS), 0, s, a, nLb,
+                       nRB, VT, MT, rm);
+  else
+    hipLaunchKernelGGL((lm_head_kernel<RBW, C, NWV, false>), dim3(JT * 8 * MT), dim3(K::THREADS), 0, s, a, nLb,
+                       nRB, VT, MT, rm);
   return hipGetLastError();
 }
 
@@ -734,7 +752,10 @@ hipError_t launch_gemm8(const LmHeadArgs& a, hipStream_t s) {
   using K = Gemm8Cfg<C>;
   const int nLb = (a.L + 31) / 32;
   const int VT = (a.n + K::BN - 1) / K::BN;
-  hipLaunchKernelGGL((lm_head_gemm8_kernel<C>), dim3(VT), dim3(K::THREADS), 0, s, a, nLb, a.B * nLb, VT);
+  if (stream_w(a))
+    hipLaunchKernelGGL((lm_head_gemm8_kernel<C, true>), dim3(VT), dim3(K::THREADS), 0, s, a, nLb, a.B * nLb, VT);
+  else
+    hipLaunchKernelGGL((lm_head_gemm8_kernel<C, false>), dim3(VT), dim3(K::THREADS), 0, s, a, nLb, a.B * nLb, VT);
   return hipGetLastError();
 }
 
@@ -783,9 +804,10 @@ hipError_t launch_lm_head(const LmHeadArgs& a, hipStream_t s) {
 
 int lm_head_kernel_name(const LmHeadArgs& a, char* buf, size_t cap) {
   const Variant v = choose(a);
-  if (v.gemm8) return snprintf(buf, cap, "lm_head_gemm8_kernel<%d>", a.C);
-  return snprintf(buf, cap, "%s<%d, %d, %d>", v.split ? "lm_head_splitk_kernel" : "lm_head_kernel",
-                  v.rbw, a.C, v.nw);
+  const char* nt = stream_w(a) ? "true" : "false";
+  if (v.gemm8) return snprintf(buf, cap, "lm_head_gemm8_kernel<%d, %s>", a.C, nt);
+  if (v.split) return snprintf(buf, cap, "lm_head_splitk_kernel<%d, %d, %d>", v.rbw, a.C, v.nw);
+  return snprintf(buf, cap, "lm_head_kernel<%d, %d, %d, %s>", v.rbw, a.C, v.nw, nt);
 }
 
 }  // namespace scd
