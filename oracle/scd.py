@@ -181,6 +181,12 @@ class ScdOracle:
                 if 0.0 < cfg.top_p < 1.0:
                     thr_p = lg.nucleus_threshold(z, keep, cfg.top_p)
                     amb_p = _ambiguous_nucleus_ids(z, keep, cfg.top_p, self.tol_mass)
+                    # ids tied with the last kept logit to within the logit tolerance: another
+                    # rounding of the LM head may split the tie (same rule as at the top-k boundary)
+                    tol_zp = self.tol * max(1.0, abs(float(thr_p))) * (1.0 + 2.0 * cfg.cfg_lambda)
+                    near = np.nonzero(keep & (np.abs(z.astype(np.float64) - np.float64(thr_p)) <= tol_zp))[0]
+                    if near.size > 1:
+                        amb_p = np.union1d(amb_p, near)
                     keep = keep & (z >= thr_p)
                     if ov:
                         for v, kv in ov.items():

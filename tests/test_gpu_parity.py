@@ -306,6 +306,13 @@ def test_lockstep_statistics_scaled_and_C2_prefix():
     _lockstep(wl.WORKLOADS["C2"], max_steps=10, check_logits=False, diagnostics=True)
 
 
+def test_lockstep_nucleus_after_topk_C2_full():
+    # the benchmark's shape with the nucleus filter on top of top-k, the whole decode: holds rows
+    # whose boundary falls on an exact tie of two logits that the GPU's GEMM rounding splits
+    ls, st = _lockstep(wl.scaled(wl.WORKLOADS["C2"], name="C2p", top_p=0.8), check_logits=False)
+    assert ls.oracle.done()
+
+
 def test_lockstep_scaled_video():
     _lockstep(wl.scaled(wl.WORKLOADS["C4"], name="C4s", N=8 * 24, V=2000, d=512, top_k=300, L=64))
 
