@@ -48,6 +48,7 @@ def _require_gpu_and_library():
     (2, 64, 256, 52000, 0, 52000, 3.0, 1.0),
     (1, 100, 192, 51300, 5, 51290, 3.0, 1.0),   # ragged n, ragged L, odd number of k tiles
     (3, 20, 136, 51210, 0, 51210, 0.0, 0.9),    # 3 row blocks, no CFG, d not a multiple of the k tile
+    (2, 64, 128, 51200, 0, 51200, 3.0, 1.0),    # its shortest k loop: 2 tiles
 ])
 def test_lm_head_against_oracle(Bn, L, d, V, v_lo, v_hi, lam, tau):
     g = np.random.default_rng(hash((Bn, L, d, V)) % 2 ** 32)
