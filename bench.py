@@ -115,7 +115,7 @@ def cpu_baseline(w, seconds, coupling="mc", sjd_mix=0.0):
     del W
     tab = wl.HiddenTable(w)
     cfg = oscd.ScdConfig(B=w.B, L=w.L, N=w.N, V=w.V, v_lo=w.v_lo, v_hi=w.v_hi, top_k=w.top_k,
-                         temperature=w.temperature, cfg_lambda=w.cfg_lambda, seed=w.seed,
+                         top_p=w.top_p, temperature=w.temperature, cfg_lambda=w.cfg_lambda, seed=w.seed,
                          coupling=coupling, alpha=float(np.float32(1.0) - np.float32(sjd_mix)))
     o = oscd.ScdOracle(cfg)
     tab.window(list(o.i), [[0] * w.L for _ in range(w.B)])      # warm the generator caches
