@@ -332,9 +332,12 @@ def test_lockstep_C2_prefix_with_logits():
     _lockstep(wl.WORKLOADS["C2"], max_steps=12)
 
 
-def test_lockstep_C2_fullV_prefix():
+def test_lockstep_C2_fullV_full():
+    # the full-vocabulary variant of the benchmark's workload: logits checked on a prefix, then
+    # the whole decode (415 iterations, 13210 rows; the W stream uses the non-temporal loads)
     _lockstep(wl.WORKLOADS["C2-fullV"], max_steps=5)
-    _lockstep(wl.WORKLOADS["C2-fullV"], max_steps=40, check_logits=False)
+    ls, st = _lockstep(wl.WORKLOADS["C2-fullV"], check_logits=False)
+    assert ls.oracle.done() and st["steps"] == 415
 
 
 def test_lockstep_C3_prefix():
