@@ -143,13 +143,15 @@ def test_select_nucleus_against_oracle(n, top_k, top_p):
 
 
 # ------------------------------------------------------------- MRS stage
-@pytest.mark.parametrize("Bn,L,n,top_k,N,pos0", [
-    (1, 8, 1024, 0, 64, [0]),
-    (2, 16, 1000, 100, 40, [3, 30]),      # ragged n (scalar loads), second window clipped to 10 rows
-    (1, 32, 8192, 2000, 2304, [100]),
-    (3, 5, 37, 7, 50, [0, 45, 49]),       # tiny vocabulary, windows of 5 / 5 / 1 rows
+@pytest.mark.parametrize("Bn,L,n,top_k,N,pos0,top_p", [
+    (1, 8, 1024, 0, 64, [0], 0.0),
+    (2, 16, 1000, 100, 40, [3, 30], 0.0),      # ragged n (scalar loads), second window clipped to 10 rows
+    (1, 32, 8192, 2000, 2304, [100], 0.0),
+    (3, 5, 37, 7, 50, [0, 45, 49], 0.0),       # tiny vocabulary, windows of 5 / 5 / 1 rows
+    (2, 16, 4096, 500, 100, [0, 90], 0.7),     # nucleus filter after top-k
+    (1, 24, 20000, 0, 64, [5], 0.9),           # nucleus filter alone on a long row (in-place path)
 ])
-def test_couple_draft_and_verify_against_oracle(Bn, L, n, top_k, N, pos0):
+def test_couple_draft_and_verify_against_oracle(Bn, L, n, top_k, N, pos0, top_p):
     g = np.random.default_rng(n + L)
     seed, it = 0xABCDEF0123456789, 7
     base = (g.standard_normal((Bn, L, n)) * 2).astype(np.float32)
@@ -166,9 +168,9 @@ def test_couple_draft_and_verify_against_oracle(Bn, L, n, top_k, N, pos0):
             if fresh[b, s]:
                 x[b, s] = g.integers(0, n)
             else:
-                q, _, _ = lg.distribution(z_prev[b, s], top_k)
+                q, _, _ = lg.distribution(z_prev[b, s], top_k, top_p)
                 x[b, s] = g.choice(n, p=q)
-    cfg = B.make_config(B=Bn, L=L, N=N, V=n, top_k=top_k, seed=seed)
+    cfg = B.make_config(B=Bn, L=L, N=N, V=n, top_k=top_k, top_p=top_p, seed=seed)
     sc = B.Scd(cfg, DEV)
     t = lambda a: torch.from_numpy(a).to(DEV)
     y = torch.empty((Bn, L), dtype=torch.int32, device=DEV)
@@ -189,9 +191,9 @@ def test_couple_draft_and_verify_against_oracle(Bn, L, n, top_k, N, pos0):
                 assert y[b, s] == -1 and k[b, s] == 1
                 continue
             j = pos0[b] + s
-            p, _, _ = lg.distribution(z_cur[b, s], top_k)
+            p, _, _ = lg.distribution(z_cur[b, s], top_k, top_p)
             q = np.full(n, np.float64(np.float32(1.0) / np.float32(n))) if fresh[b, s] \
-                else lg.distribution(z_prev[b, s], top_k)[0]
+                else lg.distribution(z_prev[b, s], top_k, top_p)[0]
             u = philox.uniform_scalar(seed, b, j, it, philox.STREAM_ACCEPT)
             r = omrs.mrs(p, q, int(x[b, s]), u,
                          lambda: philox.uniform_per_vocab(seed, b, j, it, philox.STREAM_RESID, n))
