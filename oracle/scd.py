@@ -127,6 +127,11 @@ class ScdOracle:
         self.out = np.full((B, N), -1, dtype=np.int64)
         self.accept_hist = [[] for _ in range(B)]
         self.last_hamming = [(0, 0)] * B      # (changed drafts, surviving positions) of the last step
+        # Hamm(t + 1 - n, t + 1), n = 1..3 (Sec. 5.3 "Multi-Step Behavior"): drafts of the window
+        # after the last step against the drafts n iterations earlier, over the positions that
+        # sit in both windows; (differing, compared) per n
+        self.last_hamming_multi = [[(0, 0)] * 3 for _ in range(B)]
+        self._draft_hist = [[] for _ in range(B)]     # newest first: (window start, drafts by position)
         self.positions_verified = 0
         for b in range(B):
             for j in range(min(L, N)):
@@ -285,6 +290,7 @@ class ScdOracle:
             a = min(first_rej + 1, Lw)
             for s in range(a):
                 self.out[b, i + s] = cfg.v_lo + res[b][s]["y"]
+            self._draft_hist[b] = ([(i, self.X[b].copy())] + self._draft_hist[b])[:3]
             survivors = list(range(i + a, i + Lw))
             self.last_hamming[b] = (dg.hamming(self.X[b, survivors],
                                                [res[b][j - i]["next"] for j in survivors]), len(survivors))
@@ -297,6 +303,15 @@ class ScdOracle:
                 self.q[b].pop(i + s, None)
             for j in range(i + Lw, min(i + a + cfg.L, cfg.N)):   # entering positions
                 self._init_position(b, j)
+            multi = []
+            for n_back in range(3):
+                if n_back < len(self._draft_hist[b]):
+                    start, drafts = self._draft_hist[b][n_back]
+                    both = range(i + a, min(start + cfg.L, cfg.N))       # in the new and in that window
+                    multi.append((dg.hamming(drafts[both], self.X[b][both]), len(both)))
+                else:
+                    multi.append((0, 0))
+            self.last_hamming_multi[b] = multi
             self.positions_verified += Lw
             self.i[b] = i + a
             self.t[b] += 1

@@ -97,3 +97,33 @@ def test_hamming_of_a_decode_follows_the_coupling():
         frac[alpha] = changed / surv
         assert abs(changed - expect) < 4.5 * np.sqrt(var) + 1, (alpha, changed, expect)
     assert frac[1.0] < 0.6 * frac[0.0]
+
+
+def test_multi_step_hamming():
+    """Hamm(t - n, t) over the positions common to both windows (Sec. 5.3 "Multi-Step
+    Behavior").  n = 1 is the count of changed survivors (computed separately); with
+    independent redrafts (alpha = 0) drafts n iterations apart are independent draws, so the
+    changed fraction is about 1 - C for every n; under the maximal coupling changes accumulate:
+    the fraction grows with n but stays below the independent one."""
+    from oracle import scd
+    from paper_2510_24211_amd import workload as wl
+    w = wl.scaled(wl.WORKLOADS["C0"], N=600, L=32, V=64, seed=43, amp=2.0, decay=0.85, age_cap=24)
+    toy = wl.ToyLogits(w)
+    frac = {}
+    for alpha in (1.0, 0.0):
+        cfg = scd.ScdConfig(B=1, L=w.L, N=w.N, V=w.V, seed=w.seed, alpha=alpha)
+        o = scd.ScdOracle(cfg)
+        tot = np.zeros((3, 2))
+        coll = []
+        while not o.done():
+            i, Lw = o.window(0)
+            z = np.stack([toy.table[0, i + s, min(int(o.age[0, i + s]), w.age_cap)] for s in range(Lw)])
+            plan, res, acc = o.step([z])
+            assert o.last_hamming_multi[0][0] == o.last_hamming[0]
+            tot += np.array(o.last_hamming_multi[0])
+            coll += [res[0][s]["stats"][1] for s in range(acc[0], Lw) if o.age[0, i + s] > 1]
+        frac[alpha] = tot[:, 0] / tot[:, 1]
+        assert (tot[:, 1] > 400).all(), tot
+        if alpha == 0.0:
+            assert np.abs(frac[alpha] - (1 - np.mean(coll))).max() < 0.03
+    assert frac[1.0][0] < frac[1.0][1] < frac[1.0][2] < frac[0.0].min()
