@@ -234,7 +234,7 @@ def measure(a, name, inputs):
         return chunks[i // CH][i % CH]
 
     diag_sum = torch.zeros(4, dtype=torch.float64, device=dev)     # beta, C, bound, live rows
-    hamm_sum = torch.zeros(2, dtype=torch.int64, device=dev)       # changed drafts, survivors
+    hamm_sum = torch.zeros(6, dtype=torch.int64, device=dev)       # (differing, compared) for 1, 2, 3 iterations apart
 
     def record(limit):
         """Decode from a fresh state, at most `limit` steps; returns the iteration count."""
@@ -251,7 +251,7 @@ def measure(a, name, inputs):
                     diag_sum[1] += d[:, 1].sum()
                     diag_sum[2] += (d[:, 2] * d[:, 3]).sqrt().sum()
                     diag_sum[3] += (d[:, 2] > 0).sum()
-                    hamm_sum.add_(s.state_field(st, B.F_HAMM).view(-1, 2).sum(0))
+                    hamm_sum.add_(s.state_field(st, B.F_HAMM).view(-1, 6).sum(0))
                 i += 1
             rc, flags = s.status(st)
             assert rc == B.SCD_OK, (rc, flags)
@@ -393,7 +393,9 @@ def measure(a, name, inputs):
                               "mean_independent_collision_probability": ds[1] / rows,
                               "mean_renyi2_collision_bound": ds[2] / rows,
                               "changed_drafts": int(hs_[0]), "surviving_positions": int(hs_[1]),
-                              "hamming_fraction": float(hs_[0]) / max(float(hs_[1]), 1.0)}
+                              "hamming_fraction": float(hs_[0]) / max(float(hs_[1]), 1.0),
+                              "hamming_fraction_2_iterations_apart": float(hs_[2]) / max(float(hs_[3]), 1.0),
+                              "hamming_fraction_3_iterations_apart": float(hs_[4]) / max(float(hs_[5]), 1.0)}
     return out, w
 
 

@@ -88,7 +88,8 @@ typedef struct scd_config {
                           paper's analysis (Sec. 3: acceptance rate beta = 1 - D_TV(p, q),
                           Prop. "SJD Collision Probability": C = sum_v p_v q_v and the two
                           sums its Renyi-2 bound needs) to SCD_F_DIAG and the number of changed
-                          drafts (Hamming distance of consecutive drafts) to SCD_F_HAMM;
+                          drafts (Hamming distance between the drafts 1, 2 and 3 iterations
+                          apart, Sec. 5.3 "Multi-Step Behavior") to SCD_F_HAMM;
                           0 => off; needs v_hi - v_lo <= 65536                               */
   uint64_t seed;
 } scd_config;
@@ -140,9 +141,14 @@ typedef enum scd_field {
                                          came from (uniform for a first evaluation); rows that
                                          are not live hold zeros                             */
   SCD_F_S2 = 19,      /* float [2, B, L] internal: sum_v p_v^2 per parity and slot            */
-  SCD_F_HAMM = 20,    /* int32 [B, 2]    last step (diagnostics = 1 only): surviving window
-                                         positions whose draft changed, surviving positions   */
-  SCD_F_COUNT = 21
+  SCD_F_HAMM = 20,    /* int32 [B, 6]    last step (diagnostics = 1 only): for n = 1, 2, 3 the pair
+                                         (differing, compared) of Hamm(t + 1 - n, t + 1): the
+                                         window's drafts after the step against the drafts n
+                                         iterations earlier, over the positions in both windows
+                                         (n = 1: the surviving positions whose draft changed)  */
+  SCD_F_XHIST = 21,   /* int32 [3, B, L] internal: drafts at the start of the last 3 iterations */
+  SCD_F_PHIST = 22,   /* int32 [3, B]    internal: window starts of those iterations            */
+  SCD_F_COUNT = 23
 } scd_field;
 
 /* Bytes of caller-provided device scratch a context needs; 0 on a bad config. */

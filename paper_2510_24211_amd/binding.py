@@ -17,8 +17,8 @@ SCD_OK, SCD_EINVAL, SCD_EWORKSPACE, SCD_EHIP, SCD_ENUMERIC, SCD_EUNSUPPORTED = 0
 
 # scd_field
 (F_POS, F_ITER, F_X, F_AGE, F_OUT, F_ACCEPT, F_Y, F_K, F_PX, F_QX, F_THR, F_LSE, F_NKEPT, F_Z,
- F_FLAGS, F_VERIFIED, F_TICKET, F_G, F_DIAG, F_S2, F_HAMM) = range(21)
-F_COUNT = 21
+ F_FLAGS, F_VERIFIED, F_TICKET, F_G, F_DIAG, F_S2, F_HAMM, F_XHIST, F_PHIST) = range(23)
+F_COUNT = 23
 COUPLING_MC, COUPLING_GS = 0, 1
 
 _FIELD_DTYPE = {
@@ -27,7 +27,7 @@ _FIELD_DTYPE = {
     F_PX: torch.float32, F_QX: torch.float32, F_THR: torch.float32, F_LSE: torch.float32,
     F_NKEPT: torch.int32, F_Z: torch.float32, F_FLAGS: torch.int32, F_VERIFIED: torch.int32,
     F_TICKET: torch.int32, F_G: torch.int32, F_DIAG: torch.float32, F_S2: torch.float32,
-    F_HAMM: torch.int32,
+    F_HAMM: torch.int32, F_XHIST: torch.int32, F_PHIST: torch.int32,
 }
 
 

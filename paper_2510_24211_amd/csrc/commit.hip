@@ -72,6 +72,7 @@ __global__ void reset_kernel(const ResetArgs a) {
     a.verified[t] = 0;
     a.ticket[t] = 0;
   }
+  for (int t = gid; t < 3 * a.B; t += stride) a.phist[t] = -(1 << 30);   // no earlier iteration
   if (gid < 4) a.flags[gid] = 0;
 }
 

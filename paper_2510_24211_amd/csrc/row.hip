@@ -74,7 +74,8 @@ struct Small {
   unsigned long long mtot[NW];   // nucleus: per-wavefront masses
   unsigned long long sel_mass;
   float dred[3][NW];             // statistics: per-wavefront sums
-  int hamm;
+  int hamm[6];                   // (differing, compared) drafts 1, 2, 3 iterations apart
+  int xnew[256];                 // the sequence's new drafts by ring slot
 };
 
 // key with -0 folded onto +0, so that key order == float order for non-NaNs
@@ -1258,10 +1259,8 @@ __global__ __launch_bounds__(THREADS) void row_kernel(const int32_t* const pos_,
       if (a.mode == kRowRing && R.s == 0) a.accept_len[R.b] = 0;   // finished sequence
       if (EXTRA && a.diag != nullptr && a.mode == kRowRing) {
         *reinterpret_cast<float4*>(a.diag + R.widx * 4) = make_float4(0.f, 0.f, 0.f, 0.f);
-        if (R.s == 0) {
-          a.hamm[2 * R.b] = 0;
-          a.hamm[2 * R.b + 1] = 0;
-        }
+        if (R.s == 0)
+          for (int i = 0; i < 6; ++i) a.hamm[6 * R.b + i] = 0;
       }
     }
     return;
@@ -1406,7 +1405,6 @@ __global__ __launch_bounds__(THREADS) void row_kernel(const int32_t* const pos_,
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
     sm.last = __hip_atomic_fetch_add(&a.ticket[b], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == live - 1;
     sm.first_rej = live;
-    sm.hamm = 0;
   }
   __syncthreads();
   if (!sm.last) return;
@@ -1423,20 +1421,31 @@ __global__ __launch_bounds__(THREADS) void row_kernel(const int32_t* const pos_,
   __syncthreads();
   const int acc = min(sm.first_rej + 1, live);
   if (tid < acc) a.out[static_cast<size_t>(b) * a.N + p0 + tid] = a.v_lo + yy;
+  const bool stats = EXTRA && a.diag != nullptr;
+  const int ring = R.it % 3;
+  if (stats) {
+    // the drafts this iteration started with, by ring slot, and where its window started
+    if (tid < a.L) a.xhist[(static_cast<size_t>(ring) * a.B + b) * a.L + tid] = a.X[static_cast<size_t>(b) * a.L + tid];
+    if (tid == 0) a.phist[ring * a.B + b] = p0;
+    if (tid < 6) sm.hamm[tid] = 0;
+    __syncthreads();                 // slot tid is rewritten by another thread below
+  }
   if (tid < live) {
-    const size_t sidx = static_cast<size_t>(b) * a.L + (p0 + tid) % a.L;
+    const int slot = (p0 + tid) % a.L;
+    const size_t sidx = static_cast<size_t>(b) * a.L + slot;
+    int next;
     if (tid >= acc) {
       // survivors: the MRS output is the coupled redraft (pi_MC); under pi_GS, or when the
       // alpha-coupling switch chose the independent redraft, it is the row's Gumbel-max draw
-      const int next = (GS && gg >= 0) ? gg : yy;
-      if (EXTRA && a.diag != nullptr && next != a.X[sidx]) atomicAdd(&sm.hamm, 1);
-      a.X[sidx] = next;
+      next = (GS && gg >= 0) ? gg : yy;
       a.age_w[sidx] += 1;
     } else {
       const int np = p0 + a.L + tid;
-      a.X[sidx] = np < a.N ? init_token(a.seed, b, np, n) : -1;
+      next = np < a.N ? init_token(a.seed, b, np, n) : -1;
       a.age_w[sidx] = 0;
     }
+    a.X[sidx] = next;
+    if (stats) sm.xnew[slot] = next;
   }
   if (tid == 0) {
     a.accept_len[b] = acc;
@@ -1445,12 +1454,30 @@ __global__ __launch_bounds__(THREADS) void row_kernel(const int32_t* const pos_,
     a.verified[b] += live;
     a.ticket[b] = 0;
   }
-  if (EXTRA && a.diag != nullptr) {     // drafts that changed among the surviving positions
+  if (stats) {
+    // Hamm(t + 1 - n, t + 1), n = 1..3 (Sec. 5.3 "Multi-Step Behavior"): the new drafts against
+    // those of n iterations earlier over the positions that sit in both windows.  The thread of
+    // ring slot tid owns the position j of the new window with j % L == tid.
     __syncthreads();
-    if (tid == 0) {
-      a.hamm[2 * b] = sm.hamm;
-      a.hamm[2 * b + 1] = live - acc;
+    const int pnew = p0 + acc;
+    if (tid < a.L) {
+      const int j = pnew + (tid - pnew % a.L + a.L) % a.L;
+      if (j < a.N && j < p0 + a.L) {               // a position the step left in the window
+        const int xn = sm.xnew[tid];
+#pragma unroll
+        for (int back = 0; back < 3; ++back) {
+          const int ri = (ring + 3 - back) % 3;
+          const int ph = back == 0 ? p0 : a.phist[ri * a.B + b];
+          if (j >= ph && j < ph + a.L) {
+            const int xo = a.xhist[(static_cast<size_t>(ri) * a.B + b) * a.L + tid];
+            atomicAdd(&sm.hamm[2 * back + 1], 1);
+            if (xo != xn) atomicAdd(&sm.hamm[2 * back], 1);
+          }
+        }
+      }
     }
+    __syncthreads();
+    if (tid < 6) a.hamm[6 * b + tid] = sm.hamm[tid];
   }
 }
 

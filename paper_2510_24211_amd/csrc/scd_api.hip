@@ -69,7 +69,9 @@ Layout make_layout(const scd_config& c) {
   sz[SCD_F_G] = 4 * B * L;
   sz[SCD_F_DIAG] = 4 * 4 * B * L;
   sz[SCD_F_S2] = 4 * 2 * B * L;
-  sz[SCD_F_HAMM] = 4 * 2 * B;
+  sz[SCD_F_HAMM] = 4 * 6 * B;
+  sz[SCD_F_XHIST] = 4 * 3 * B * L;
+  sz[SCD_F_PHIST] = 4 * 3 * B;
   Layout lay;
   size_t o = 0;
   for (int f = 0; f < SCD_F_COUNT; ++f) {
@@ -154,6 +156,8 @@ int run_tail(scd_ctx* c, void* st) {
       ra.diag = field<float>(c, st, SCD_F_DIAG);
       ra.s2 = field<float>(c, st, SCD_F_S2);
       ra.hamm = field<int32_t>(c, st, SCD_F_HAMM);
+      ra.xhist = field<int32_t>(c, st, SCD_F_XHIST);
+      ra.phist = field<int32_t>(c, st, SCD_F_PHIST);
     }
     return hip_rc(scd::launch_row(ra, c->stream));
   }
@@ -268,6 +272,7 @@ int scd_reset(scd_ctx* c, void* st) {
   a.verified = field<int32_t>(c, st, SCD_F_VERIFIED);
   a.flags = field<int32_t>(c, st, SCD_F_FLAGS);
   a.ticket = field<int32_t>(c, st, SCD_F_TICKET);
+  a.phist = field<int32_t>(c, st, SCD_F_PHIST);
   a.B = c->cfg.B; a.L = c->cfg.L; a.N = c->cfg.N; a.n = c->n; a.seed = c->cfg.seed;
   return hip_rc(scd::launch_reset(a, c->stream));
 }

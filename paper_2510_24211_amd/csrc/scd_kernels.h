@@ -108,7 +108,9 @@ struct RowArgs {
   // per-position statistics (ring mode only; all three null => off)
   float* diag;           // [B, L, 4] window order: sum min(p,q), sum p q, sum p^2, sum q^2
   float* s2;             // [2, B, L] sum p^2 per parity and slot
-  int32_t* hamm;         // [B, 2]    changed drafts, surviving positions
+  int32_t* hamm;         // [B, 6]    (differing, compared) drafts 1, 2, 3 iterations apart
+  int32_t* xhist;        // [3, B, L] drafts at the start of the last three iterations, by ring slot
+  int32_t* phist;        // [3, B]    window start of those iterations (far negative: none)
   uint64_t seed;
   // scratch for the slice kernel (rows longer than 8192 ids): row_candidate_bytes(rows)
   // bytes of device memory, 256-byte aligned, or null (then rows are processed whole)
@@ -141,6 +143,7 @@ hipError_t launch_commit(const CommitArgs& a, hipStream_t s);
 struct ResetArgs {
   int32_t* pos; int32_t* iter; int32_t* X; int32_t* age; int32_t* out; int32_t* accept_len;
   int32_t* verified; int32_t* flags; int32_t* ticket;
+  int32_t* phist;        // [3, B] -> far negative
   int B, L, N, n;
   uint64_t seed;
 };

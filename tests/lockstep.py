@@ -254,11 +254,13 @@ class LockStep:
         # ---- commit --------------------------------------------------------
         acc = o.commit(plan, res)
         if self.diagnostics:
-            gh = g["hamm"].reshape(Bn, 2)
+            gh = g["hamm"].reshape(Bn, 3, 2)
             for b in range(Bn):
                 if lives[b]:
-                    assert tuple(int(x) for x in gh[b]) == o.last_hamming[b], \
-                        f"changed drafts differ: gpu {gh[b]} oracle {o.last_hamming[b]}"
+                    want = [tuple(x) for x in o.last_hamming_multi[b]]
+                    got = [tuple(int(x) for x in pair) for pair in gh[b]]
+                    assert got == want, f"changed drafts differ: gpu {got} oracle {want}"
+                    assert got[0] == o.last_hamming[b]
                 else:
                     assert not gh[b].any()
         assert list(g["acc"]) == acc, f"accept lengths differ: {list(g['acc'])} vs {acc}"

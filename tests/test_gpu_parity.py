@@ -297,6 +297,9 @@ def test_lockstep_nucleus_scaled_and_video_prefix():
     (dict(N=16, L=4, seed=38, V=20000, age_cap=4), dict()),                # in-place path
     (dict(N=16, L=4, seed=39, V=40000, top_k=2000, age_cap=4), dict()),    # slice kernel + candidates
     (dict(N=40, L=8, seed=40, V=3000, top_p=0.8), dict()),                 # with the nucleus filter
+    (dict(N=300, L=128, seed=41, V=512), dict()),                          # window longer than a wavefront
+    (dict(N=70, L=8, seed=42, B=3, V=1000), dict(sjd_mix=1.0)),            # vanilla SJD, ragged finish
+    (dict(N=600, L=256, seed=44, V=256, age_cap=6), dict()),               # the longest window
 ])
 def test_lockstep_statistics_toy_variants(kw, opts):
     ls, st = _lockstep(wl.scaled(wl.WORKLOADS["C0"], name="toy", **kw), diagnostics=True, **opts)
