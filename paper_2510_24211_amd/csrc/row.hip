@@ -1517,7 +1517,14 @@ hipError_t launch_row(const RowArgs& a_in, hipStream_t s) {
     if (hipError_t e = hipGetLastError(); e != hipSuccess) return e;
   }
   const size_t lds = lds_bytes_for(a.n);
-  static size_t configured = 0;          // grows monotonically; benign if raced (idempotent call)
+  // the attribute belongs to the function ON A DEVICE: remembered per device.  Grows
+  // monotonically; benign if raced (the call is idempotent).
+  constexpr int kMaxDevices = 64;
+  static size_t configured_on[kMaxDevices] = {};
+  int dev = 0;
+  if (hipError_t e = hipGetDevice(&dev); e != hipSuccess) return e;
+  size_t none = 0;
+  size_t& configured = (dev >= 0 && dev < kMaxDevices) ? configured_on[dev] : none;
   if (lds > configured) {
     for (const void* f : {reinterpret_cast<const void*>(row_kernel<false, false>),
                           reinterpret_cast<const void*>(row_kernel<true, false>),
