@@ -85,10 +85,12 @@ __device__ __forceinline__ uint32_t zkey(float f) { return float_to_key(f == 0.f
 // from the top bin; lowers `need` by the population of the bins above it.
 // The trailing barrier keeps a later writer of sel_bin / sel_above / wtot away from slow
 // readers; a caller whose next such write comes after another barrier anyway may drop it.
+// T: threads of the workgroup (the row kernel's, or the slice kernel's smaller one).
+template <int T = THREADS>
 __device__ __forceinline__ uint32_t find_bin(const uint32_t* hist, uint32_t& need, Small& sm,
                                              bool trailing = true) {
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  constexpr int PER = NBINS / THREADS;   // 4 consecutive bins per thread, top bins in thread 0
+  constexpr int PER = NBINS / T;         // consecutive bins per thread, top bins in thread 0
   uint32_t c[PER], local = 0;
 #pragma unroll
   for (int j = 0; j < PER; ++j) {
@@ -121,9 +123,10 @@ __device__ __forceinline__ uint32_t find_bin(const uint32_t* hist, uint32_t& nee
   return bin;
 }
 
+template <int T = THREADS>
 __device__ __forceinline__ void zero_hist(uint32_t* hist) {
 #pragma unroll
-  for (int j = 0; j < NBINS / THREADS; ++j) hist[threadIdx.x + j * THREADS] = 0u;
+  for (int j = 0; j < NBINS / T; ++j) hist[threadIdx.x + j * T] = 0u;
 }
 
 __device__ __forceinline__ float prob(float z, float thr, float lse) {
@@ -133,6 +136,7 @@ __device__ __forceinline__ float prob(float z, float thr, float lse) {
 // Exclusive offset of this thread's `cnt` in a fixed thread order, and the total.
 // `slot` picks one of two exchange arrays; without the trailing barrier the caller must
 // have another barrier between this call and the next one on the same slot.
+template <int T = THREADS>
 __device__ __forceinline__ int block_offsets(int cnt, int& total, Small& sm, int slot = 0,
                                              bool trailing = true) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -143,7 +147,7 @@ __device__ __forceinline__ int block_offsets(int cnt, int& total, Small& sm, int
   int base = 0;
   total = 0;
 #pragma unroll
-  for (int w = 0; w < NW; ++w) {
+  for (int w = 0; w < T / kWave; ++w) {
     base += w < wave ? ex[w] : 0;
     total += ex[w];
   }
@@ -152,6 +156,7 @@ __device__ __forceinline__ int block_offsets(int cnt, int& total, Small& sm, int
 }
 
 // max / min of keys over the workgroup
+template <int T = THREADS>
 __device__ __forceinline__ void block_minmax(uint32_t& kmin, uint32_t& kmax, Small& sm,
                                              bool trailing = true) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -163,7 +168,7 @@ __device__ __forceinline__ void block_minmax(uint32_t& kmin, uint32_t& kmax, Sma
   }
   __syncthreads();
 #pragma unroll
-  for (int w = 0; w < NW; ++w) {
+  for (int w = 0; w < T / kWave; ++w) {
     kmax = sm.umax[w] > kmax ? sm.umax[w] : kmax;
     kmin = sm.umin[w] < kmin ? sm.umin[w] : kmin;
   }
@@ -181,7 +186,7 @@ __device__ __forceinline__ void block_minmax(uint32_t& kmin, uint32_t& kmax, Sma
 //   Should that bin hold more than NBINS members (massive ties), radix levels over
 //   the key bits finish the job.
 constexpr float kRangeFloor = -1.0e30f;
-template <int PER>
+template <int PER, int T = THREADS>
 __device__ __forceinline__ uint32_t select_regs(const float (&zv)[PER], const uint32_t (&kv)[PER],
                                                 const bool (&ok)[PER], uint32_t kmin_in,
                                                 uint32_t kmax, uint32_t need, uint32_t* hist,
@@ -206,7 +211,7 @@ __device__ __forceinline__ uint32_t select_regs(const float (&zv)[PER], const ui
     if (ok[e]) atomicAdd(&hist[bin[e]], 1u);
   __syncthreads();
   // no trailing barrier: sel_bin is next written after the barrier that follows the append
-  const int b1 = static_cast<int>(find_bin(hist, need, sm, false));
+  const int b1 = static_cast<int>(find_bin<T>(hist, need, sm, false));
   const uint32_t members = hist[b1];
   if (members <= static_cast<uint32_t>(NBINS)) {
 #pragma unroll
@@ -235,7 +240,7 @@ __device__ __forceinline__ uint32_t select_regs(const float (&zv)[PER], const ui
   for (;;) {
     int s2 = 0;
     while (((width - 1) >> s2) >= static_cast<uint64_t>(NBINS)) ++s2;
-    zero_hist(hist);
+    zero_hist<T>(hist);
     __syncthreads();
 #pragma unroll
     for (int e = 0; e < PER; ++e) {
@@ -243,7 +248,7 @@ __device__ __forceinline__ uint32_t select_regs(const float (&zv)[PER], const ui
         atomicAdd(&hist[(kv[e] - lo) >> s2], 1u);
     }
     __syncthreads();
-    const uint32_t dgt = find_bin(hist, need, sm);
+    const uint32_t dgt = find_bin<T>(hist, need, sm);
     lo += dgt << s2;
     width = 1ull << s2;
     if (s2 == 0) return lo;
@@ -450,13 +455,17 @@ __device__ __forceinline__ RowRef locate_row(const RowArgs& a, int r, const int3
 // ---------------------------------------------------------------------------------
 // slice kernel
 // ---------------------------------------------------------------------------------
-__global__ __launch_bounds__(THREADS) void slice_kernel(const int32_t* const pos_, const int32_t* const iter_,
+// ST threads: 1024, or 512 when there are more slices than two per CU (four such workgroups
+// fit a CU by LDS and wavefronts, so that all of them run at once: C4 192 -> 186 us per step)
+template <int ST>
+__global__ __launch_bounds__(ST) void slice_kernel(const int32_t* const pos_, const int32_t* const iter_,
                                                         const int mode_, const int L_, const int N_,
                                                         const int P, const int capE, const int rank,
                                                         const RowArgs a) {
   __shared__ uint32_t hist[NBINS];
   __shared__ uint32_t arr[NBINS];
   __shared__ Small sm;
+  constexpr int PS = kSliceMax / ST;   // logits per thread
   const int tid = threadIdx.x;
   const int r = blockIdx.x / P, p = blockIdx.x % P;
   const RowRef R = locate_row(a, r, pos_, iter_, mode_, L_, N_);
@@ -475,12 +484,12 @@ __global__ __launch_bounds__(THREADS) void slice_kernel(const int32_t* const pos
     return;
   }
   const bool vec_ok = (n & 3) == 0;
-  float zv[PER_SLICE];
-  int vid[PER_SLICE];
-  bool ok[PER_SLICE];
+  float zv[PS];
+  int vid[PS];
+  bool ok[PS];
 #pragma unroll
-  for (int u = 0; u < PER_SLICE / 4; ++u) {
-    const int v0 = lo_id + ((tid + u * THREADS) << 2);
+  for (int u = 0; u < PS / 4; ++u) {
+    const int v0 = lo_id + ((tid + u * ST) << 2);
     if (vec_ok && v0 + 3 < hi_id) {
       const float4 t = *reinterpret_cast<const float4*>(R.zc + v0);
       zv[u * 4 + 0] = t.x; zv[u * 4 + 1] = t.y; zv[u * 4 + 2] = t.z; zv[u * 4 + 3] = t.w;
@@ -494,9 +503,9 @@ __global__ __launch_bounds__(THREADS) void slice_kernel(const int32_t* const pos
       ok[u * 4 + e] = v0 + e < hi_id;
     }
   }
-  uint32_t kv[PER_SLICE], kmax = 0, kmin = 0xFFFFFFFFu;
+  uint32_t kv[PS], kmax = 0, kmin = 0xFFFFFFFFu;
 #pragma unroll
-  for (int e = 0; e < PER_SLICE; ++e) {
+  for (int e = 0; e < PS; ++e) {
     kv[e] = zkey(zv[e]);
     if (ok[e]) {
       kmax = kv[e] > kmax ? kv[e] : kmax;
@@ -504,20 +513,20 @@ __global__ __launch_bounds__(THREADS) void slice_kernel(const int32_t* const pos
       if (zv[e] != zv[e] && a.flags) atomicOr(a.flags, 1);     // NaN of either sign
     }
   }
-  zero_hist(hist);                        // published by the barrier inside block_minmax
-  block_minmax(kmin, kmax, sm, false);
+  zero_hist<ST>(hist);                        // published by the barrier inside block_minmax
+  block_minmax<ST>(kmin, kmax, sm, false);
   const int nvalid = hi_id - lo_id;
   uint32_t cut = 0;                       // 0: the whole slice is emitted
   if (nvalid > rank)
-    cut = select_regs<PER_SLICE>(zv, kv, ok, kmin, kmax, static_cast<uint32_t>(rank), hist, arr, sm);
+    cut = select_regs<PS, ST>(zv, kv, ok, kmin, kmax, static_cast<uint32_t>(rank), hist, arr, sm);
   int mine = 0;
 #pragma unroll
-  for (int e = 0; e < PER_SLICE; ++e) mine += (ok[e] && kv[e] >= cut) ? 1 : 0;
+  for (int e = 0; e < PS; ++e) mine += (ok[e] && kv[e] >= cut) ? 1 : 0;
   int total;
-  int off = block_offsets(mine, total, sm, 0, false);
+  int off = block_offsets<ST>(mine, total, sm, 0, false);
   uint2* const dst = a.cand + (static_cast<size_t>(r) * kListCap + static_cast<size_t>(p) * capE);
 #pragma unroll
-  for (int e = 0; e < PER_SLICE; ++e) {
+  for (int e = 0; e < PS; ++e) {
     if (ok[e] && kv[e] >= cut) {
       if (off < capE) dst[off] = make_uint2(static_cast<uint32_t>(vid[e]), __float_as_uint(zv[e]));
       ++off;
@@ -1512,8 +1521,12 @@ hipError_t launch_row(const RowArgs& a_in, hipStream_t s) {
     a.cand = reinterpret_cast<uint2*>(base);
     a.cand_cnt = reinterpret_cast<uint32_t*>(base + pairs);
     a.cand_cut = reinterpret_cast<uint32_t*>(base + pairs + small_block(a.rows));
-    hipLaunchKernelGGL(slice_kernel, dim3(a.rows * P), dim3(THREADS), 0, s, a.pos, a.iter, a.mode, a.L, a.N, P,
-                       capE, rank, a);
+    if (a.rows * P > 512)
+      hipLaunchKernelGGL(slice_kernel<512>, dim3(a.rows * P), dim3(512), 0, s, a.pos, a.iter, a.mode, a.L, a.N, P,
+                         capE, rank, a);
+    else
+      hipLaunchKernelGGL(slice_kernel<THREADS>, dim3(a.rows * P), dim3(THREADS), 0, s, a.pos, a.iter, a.mode, a.L,
+                         a.N, P, capE, rank, a);
     if (hipError_t e = hipGetLastError(); e != hipSuccess) return e;
   }
   const size_t lds = lds_bytes_for(a.n);
