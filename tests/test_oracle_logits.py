@@ -188,3 +188,25 @@ def test_nucleus_ties_are_never_split():
     assert (z >= thr).sum() == 4
     thr = lg.nucleus_threshold(z, np.ones(4, dtype=bool), 0.3)
     assert (z >= thr).sum() == 1
+
+
+def test_nucleus_is_monotone_and_nested_in_p():
+    """A larger target mass never raises the threshold: the kept sets are nested, and their
+    masses bracket the targets (property over random rows, ties included)."""
+    g = np.random.default_rng(8)
+    for trial in range(40):
+        n = int(g.integers(3, 400))
+        z = (g.standard_normal(n) * g.uniform(0.2, 4.0)).astype(np.float32)
+        if trial % 4 == 0:
+            z = (np.round(z * 2) / 2).astype(np.float32)          # many exact ties
+        every = np.ones(n, dtype=bool)
+        p_full = special.softmax(z.astype(np.float64))
+        prev_thr, prev_kept = np.inf, 0
+        for top_p in np.sort(g.uniform(0.01, 0.99, size=12)):
+            thr = lg.nucleus_threshold(z, every, float(top_p))
+            kept = z >= thr
+            assert thr <= prev_thr and kept.sum() >= prev_kept
+            assert p_full[kept].sum() >= top_p - 1e-12
+            strictly_above = z > thr                               # without the last level: too little
+            assert p_full[strictly_above].sum() < top_p + 1e-12
+            prev_thr, prev_kept = thr, int(kept.sum())

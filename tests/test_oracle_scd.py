@@ -151,6 +151,19 @@ def test_vectorised_equals_sequential_on_C0_and_small_cases():
             assert sum(hist[b]) == cfg.N and all(1 <= a <= cfg.L for a in hist[b])
 
 
+def test_vectorised_equals_sequential_with_every_option_combined():
+    """Top-k, nucleus, both couplings and the alpha switch together: the two forms of the
+    decode reach each processor through different functions and must emit the same tokens."""
+    for coupling, alpha, kw in [("gs", 1.0, dict(N=24, L=6, seed=51, top_k=40, top_p=0.7)),
+                                ("mc", 0.4, dict(N=24, L=6, seed=52, top_p=0.9)),
+                                ("gs", 0.6, dict(N=20, L=5, seed=53, top_k=30, top_p=0.5, B=2))]:
+        w, cfg, model = _toy(**kw)
+        cfg.coupling, cfg.alpha = coupling, alpha
+        o = scd.decode(cfg, model)
+        out, nfe, hist = scd.decode_sequential(cfg, model)
+        assert np.array_equal(o.out, out) and o.t == nfe and o.accept_hist == hist
+
+
 def test_C0_decodes_and_speculation_helps():
     w, cfg, model = _toy()
     o = scd.decode(cfg, model)
