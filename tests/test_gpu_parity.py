@@ -306,6 +306,14 @@ def test_lockstep_statistics_toy_variants(kw, opts):
     assert st["max_stat_rel"] < 2e-5
 
 
+def test_lockstep_every_option_combined():
+    # top-k, nucleus, Gumbel sharing, the alpha switch and the statistics in one decode
+    _lockstep(wl.scaled(wl.WORKLOADS["C0"], name="toy", N=80, L=16, seed=45, V=5000, top_k=800, top_p=0.85, B=2),
+              coupling="gs", sjd_mix=0.3, diagnostics=True)
+    _lockstep(wl.scaled(wl.WORKLOADS["C2"], name="C2o", N=64, V=4096, d=320, v_lo=100, v_hi=3000, top_k=300,
+                        top_p=0.9), coupling="gs", sjd_mix=0.5, diagnostics=True)
+
+
 def test_lockstep_statistics_scaled_and_C2_prefix():
     _lockstep(wl.scaled(wl.WORKLOADS["C3"], name="C3s", B=4, N=80, V=4096, d=256, v_lo=4, v_hi=1028,
                         top_k=250), diagnostics=True)
