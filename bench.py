@@ -11,8 +11,9 @@ resident in HBM before the timed region starts; nothing crosses PCIe inside it.
 Prints ONE JSON line.  `value` = window positions verified per second over the
 timed steps; `tokens_per_s` = emitted tokens per second over the same steps.
 `roofline` describes the dominant kernel (the LM-head stream over W), timed with
-HIP events recorded inside scd_step on the stream it runs on, in a repeat of the
-timed steps (the events themselves slow a step by several microseconds, so `value`
+HIP events attached to the LM-head dispatch inside scd_step (they take the kernel's own
+start and stop time on the stream it runs on), in a repeat of the timed steps (a step
+launched that way is about a microsecond slower, so `value`
 comes from the pass without them; `config.ms_per_step_with_events` is the other).  `cpu_baseline`
 is the NumPy oracle timed on the host cores on a bounded sample of the same
 workload.
@@ -77,10 +78,9 @@ class HipEvents:
         self.ev = []
         for _ in range(2 * n):
             e = ctypes.c_void_p()
-            # hipEventDisableSystemFence: recording such an event does not flush the caches to
-            # system scope (nothing is read by the host at these points: the stream is
-            # synchronised before any result is read).  With the default flags each pair adds
-            # about 3 us to the interval it brackets, with this one about 1.5 us.
+            # hipEventDisableSystemFence: such an event does not flush the caches to system scope
+            # (nothing is read by the host at these points: the stream is synchronised before
+            # any result is read).
             assert self.hip.hipEventCreateWithFlags(ctypes.byref(e), 0x20000000) == 0
             self.ev.append(e)
 
@@ -314,7 +314,8 @@ def measure(a, name, inputs):
             assert torch.equal(s.state_field(st, B.F_OUT), tokens_ref), "decode is not reproducible"
         return T, verified, tokens
 
-    # The event pairs cost about 6 us per step (two more packets on the stream between the
+    # A step whose LM head carries the events is about a microsecond slower (the dispatch then
+    # reports its timestamps; recorded event PAIRS cost 2-6 us: two more packets between the
     # kernels), so the throughput comes from a pass without them and the LM-head timing from
     # an identical pass with them, right after (--events-in-step: one pass for both).
     T_ev = None

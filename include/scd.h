@@ -216,9 +216,11 @@ int scd_verify(scd_ctx* ctx, const uint8_t* d_k, const int32_t* d_y, const int32
 int scd_step(scd_ctx* ctx, const uint16_t* d_h, const uint16_t* d_W, void* d_state);
 
 /* Optional instrumentation for benchmarks: while both events are non-NULL,
- * scd_step records ev_start immediately before and ev_stop immediately after
- * the LM-head kernel on the context's stream (hipEvent_t passed as void*, owned
- * by the caller).  NULL, NULL turns it off.  Host-only call. */
+ * scd_step launches the LM-head kernel with the two events attached to the
+ * dispatch (hipExtLaunchKernel): ev_start takes the kernel's start time, ev_stop
+ * its stop time, on the context's stream; no other packet enters the stream
+ * (hipEvent_t passed as void*, owned by the caller).  NULL, NULL turns it off.
+ * Host-only call. */
 int scd_set_lm_head_events(scd_ctx* ctx, void* ev_start, void* ev_stop);
 
 /* For reports: writes the name of the LM-head kernel that scd_step / scd_lm_head launch

@@ -32,6 +32,8 @@
 //     the end (a fixed order: deterministic).
 #include "scd_kernels.h"
 
+#include <hip/hip_ext.h>
+
 #include <stdio.h>
 
 namespace scd {
@@ -709,11 +711,22 @@ RowMap make_row_map(const LmHeadArgs& a, int BN, int VT, bool affine, int* tiles
   return m;
 }
 
+// Optional timing of the launch: the runtime attaches the two events to the dispatch itself
+// (start and stop time of the kernel), so no marker packets of their own enter the stream.
+struct LaunchEvents {
+  hipEvent_t start, stop;
+};
+template <class Kern, class... Args>
+void launch_kernel(Kern kernel, dim3 grid, dim3 block, hipStream_t s, const LaunchEvents& ev, Args... args) {
+  if (ev.start && ev.stop) hipExtLaunchKernelGGL(kernel, grid, block, 0, s, ev.start, ev.stop, 0, args...);
+  else hipLaunchKernelGGL(kernel, grid, block, 0, s, args...);
+}
+
 // W is streamed past the caches when its slice cannot stay in the memory-side cache anyway
 bool stream_w(const LmHeadArgs& a) { return 2.0 * a.d * a.n > 192.0 * 1024 * 1024; }
 
 template <int RBW, int C, int NWV>
-hipError_t launch_wide(const LmHeadArgs& a, hipStream_t s) {
+hipError_t launch_wide(const LmHeadArgs& a, hipStream_t s, const LaunchEvents& ev) {
   using K = Cfg<RBW, C, NWV>;
   const int nLb = (a.L + 31) / 32;
   const int nRB = a.B * nLb;
@@ -725,16 +738,16 @@ hipError_t launch_wide(const LmHeadArgs& a, hipStream_t s) {
   // against 94 us for the full vocabulary), so rows stay consecutive here.
   const RowMap rm = make_row_map(a, K::BN, VT, false, &JT);
   if (stream_w(a))
-    hipLaunchKernelGGL((lm_head_kernel<RBW, C, NWV, true>), dim3(JT * 8 * MT), dim3(K::THREADS), 0, s, a, nLb,
-                       nRB, VT, MT, rm);
+    launch_kernel(lm_head_kernel<RBW, C, NWV, true>, dim3(JT * 8 * MT), dim3(K::THREADS), s, ev, a, nLb, nRB, VT,
+                  MT, rm);
   else
-    hipLaunchKernelGGL((lm_head_kernel<RBW, C, NWV, false>), dim3(JT * 8 * MT), dim3(K::THREADS), 0, s, a, nLb,
-                       nRB, VT, MT, rm);
+    launch_kernel(lm_head_kernel<RBW, C, NWV, false>, dim3(JT * 8 * MT), dim3(K::THREADS), s, ev, a, nLb, nRB, VT,
+                  MT, rm);
   return hipGetLastError();
 }
 
 template <int RBW, int C, int KS>
-hipError_t launch_split(const LmHeadArgs& a, hipStream_t s) {
+hipError_t launch_split(const LmHeadArgs& a, hipStream_t s, const LaunchEvents& ev) {
   using K = SplitCfg<RBW, C, KS>;
   const int nLb = (a.L + 31) / 32;
   const int nRB = a.B * nLb;
@@ -742,20 +755,20 @@ hipError_t launch_split(const LmHeadArgs& a, hipStream_t s) {
   const int MT = (nRB + RBW - 1) / RBW;
   int JT;
   const RowMap rm = make_row_map(a, 32, VT, true, &JT);
-  hipLaunchKernelGGL((lm_head_splitk_kernel<RBW, C, KS>), dim3(JT * 8 * MT), dim3(K::THREADS), 0, s, a.W, a.h,
-                     a.d, a.n, a.L, nLb, nRB, MT, rm.gshift, rm.rot, a);
+  launch_kernel(lm_head_splitk_kernel<RBW, C, KS>, dim3(JT * 8 * MT), dim3(K::THREADS), s, ev, a.W, a.h, a.d, a.n,
+                a.L, nLb, nRB, MT, rm.gshift, rm.rot, a);
   return hipGetLastError();
 }
 
 template <int C>
-hipError_t launch_gemm8(const LmHeadArgs& a, hipStream_t s) {
+hipError_t launch_gemm8(const LmHeadArgs& a, hipStream_t s, const LaunchEvents& ev) {
   using K = Gemm8Cfg<C>;
   const int nLb = (a.L + 31) / 32;
   const int VT = (a.n + K::BN - 1) / K::BN;
   if (stream_w(a))
-    hipLaunchKernelGGL((lm_head_gemm8_kernel<C, true>), dim3(VT), dim3(K::THREADS), 0, s, a, nLb, a.B * nLb, VT);
+    launch_kernel(lm_head_gemm8_kernel<C, true>, dim3(VT), dim3(K::THREADS), s, ev, a, nLb, a.B * nLb, VT);
   else
-    hipLaunchKernelGGL((lm_head_gemm8_kernel<C, false>), dim3(VT), dim3(K::THREADS), 0, s, a, nLb, a.B * nLb, VT);
+    launch_kernel(lm_head_gemm8_kernel<C, false>, dim3(VT), dim3(K::THREADS), s, ev, a, nLb, a.B * nLb, VT);
   return hipGetLastError();
 }
 
@@ -785,21 +798,22 @@ Variant choose(const LmHeadArgs& a) {
 }
 
 template <int C>
-hipError_t launch_c(const LmHeadArgs& a, hipStream_t s) {
+hipError_t launch_c(const LmHeadArgs& a, hipStream_t s, const LaunchEvents& ev) {
   const Variant v = choose(a);
-  if (v.gemm8) return launch_gemm8<C>(a, s);
+  if (v.gemm8) return launch_gemm8<C>(a, s, ev);
   if (v.split) {
-    if (v.rbw == 2) return launch_split<2, C, 4>(a, s);
-    return v.nw == 8 ? launch_split<1, C, 8>(a, s) : launch_split<1, C, 4>(a, s);
+    if (v.rbw == 2) return launch_split<2, C, 4>(a, s, ev);
+    return v.nw == 8 ? launch_split<1, C, 8>(a, s, ev) : launch_split<1, C, 4>(a, s, ev);
   }
-  if (v.rbw == 2) return launch_wide<2, C, 4>(a, s);
-  return v.nw == 8 ? launch_wide<1, C, 8>(a, s) : launch_wide<1, C, 4>(a, s);
+  if (v.rbw == 2) return launch_wide<2, C, 4>(a, s, ev);
+  return v.nw == 8 ? launch_wide<1, C, 8>(a, s, ev) : launch_wide<1, C, 4>(a, s, ev);
 }
 
 }  // namespace
 
-hipError_t launch_lm_head(const LmHeadArgs& a, hipStream_t s) {
-  return a.C == 2 ? launch_c<2>(a, s) : launch_c<1>(a, s);
+hipError_t launch_lm_head(const LmHeadArgs& a, hipStream_t s, hipEvent_t ev_start, hipEvent_t ev_stop) {
+  const LaunchEvents ev{ev_start, ev_stop};
+  return a.C == 2 ? launch_c<2>(a, s, ev) : launch_c<1>(a, s, ev);
 }
 
 int lm_head_kernel_name(const LmHeadArgs& a, char* buf, size_t cap) {

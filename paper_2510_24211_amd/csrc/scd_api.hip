@@ -384,9 +384,9 @@ int scd_step(scd_ctx* c, const uint16_t* d_h, const uint16_t* d_W, void* st) {
   a.one_plus_lam = 1.0f + c->cfg.cfg_lambda;
   a.tau = c->cfg.temperature;
   const bool timed = c->ev_start && c->ev_stop;
-  if (timed && hipEventRecord(c->ev_start, c->stream) != hipSuccess) return SCD_EHIP;
-  if (hipError_t e = scd::launch_lm_head(a, c->stream); e != hipSuccess) return SCD_EHIP;
-  if (timed && hipEventRecord(c->ev_stop, c->stream) != hipSuccess) return SCD_EHIP;
+  if (hipError_t e = scd::launch_lm_head(a, c->stream, timed ? c->ev_start : nullptr, timed ? c->ev_stop : nullptr);
+      e != hipSuccess)
+    return SCD_EHIP;
   return run_tail(c, st);
 }
 

@@ -18,7 +18,9 @@ struct LmHeadArgs {
   int B, C, L, N, d, n;
   float lam, one_plus_lam, tau;
 };
-hipError_t launch_lm_head(const LmHeadArgs& a, hipStream_t s);
+// ev_start / ev_stop (both or neither): events that take the kernel's own start and stop time
+hipError_t launch_lm_head(const LmHeadArgs& a, hipStream_t s, hipEvent_t ev_start = nullptr,
+                          hipEvent_t ev_stop = nullptr);
 // Name (as a profiler prints it, without namespaces and arguments) of the kernel that
 // launch_lm_head picks for these sizes (only B, C, L, d, n are read); snprintf semantics.
 int lm_head_kernel_name(const LmHeadArgs& a, char* buf, size_t cap);
