@@ -87,11 +87,14 @@ class ScdConfig:
 
 
 def _ambiguous_ids(z, thr, top_k, tol_z):
-    """Ids whose membership in the top-k set could flip under a logit
-    perturbation of tol_z: every id within tol_z of the threshold, the K-th
-    itself included (an exact tie here may be split elsewhere), provided there
-    is more than one such id."""
-    if top_k <= 0 or top_k >= z.shape[-1]:
+    """Ids whose membership in the top-k set could differ in an implementation
+    whose logits are within tol_z / 2 of z (sup norm): every id within tol_z of
+    the threshold, the K-th itself included (an exact tie here may be split
+    there), provided there is more than one such id.  Why tol_z = 2 * error is
+    exact: an order statistic moves by at most the sup-norm error e, and so does
+    every logit, so z_v >= thr can change only where |z_v - thr| <= 2 e.
+    tol_z <= 0 (bit-identical logits): nothing is ambiguous."""
+    if top_k <= 0 or top_k >= z.shape[-1] or not tol_z > 0.0:
         return np.zeros(0, dtype=np.int64)
     d = np.abs(z.astype(np.float64) - np.float64(thr))
     ids = np.nonzero(d <= tol_z)[0]
@@ -124,6 +127,7 @@ class ScdOracle:
         self.X = np.full((B, N + L), -1, dtype=np.int64)      # current draft per position
         self.age = np.zeros((B, N + L), dtype=np.int64)       # evaluations so far
         self.q = [dict() for _ in range(B)]   # pos -> fp64 row of the draft distribution
+        self.qerr = [dict() for _ in range(B)]  # pos -> logit discrepancy bound that row was flagged with
         self.out = np.full((B, N), -1, dtype=np.int64)
         self.accept_hist = [[] for _ in range(B)]
         self.last_hamming = [(0, 0)] * B      # (changed drafts, surviving positions) of the last step
@@ -142,6 +146,7 @@ class ScdOracle:
         self.X[b, j] = philox.init_token(self.cfg.seed, b, j, self.cfg.n_allowed)
         self.age[b, j] = 0
         self.q[b].pop(j, None)
+        self.qerr[b].pop(j, None)
 
     def window(self, b):
         i = self.i[b]
@@ -160,12 +165,21 @@ class ScdOracle:
         return np.full(n, np.float64(np.float32(1.0) / np.float32(n)))
 
     # -- phase 1: distributions ---------------------------------------------
-    def evaluate(self, z_rows, keep_override=None):
+    def evaluate(self, z_rows, keep_override=None, logit_err=None):
         """z_rows[b]: fp32 [Lw_b, |A|] processed logits of the window
         (after CFG, mask, temperature).  Returns plan[b][s] =
-        dict(p, thr, lse, nkept, ambiguous).  thr is the smallest kept logit when a
+        dict(p, thr, lse, nkept, ambiguous, err).  thr is the smallest kept logit when a
         filter removed something, else -inf.  keep_override[(b, position)] = {id: kept}
-        forces the membership of ids listed as ambiguous (top-k stage, then nucleus stage)."""
+        forces the membership of ids listed as ambiguous (top-k stage, then nucleus stage).
+
+        Flags (what a second implementation may legitimately decide differently):
+        logit_err[b][s] = sup-norm distance between this row's logits and the other
+        implementation's (0 for bit-identical logits).  Ids within 2 * logit_err of a
+        filter threshold are ambiguous (see _ambiguous_ids); a cumulative nucleus mass
+        may be off by tol_mass + 2 * logit_err (every normalised probability moves by a
+        factor within exp(+-2 e)).  Without logit_err an a-priori band is used:
+        tol * (1 + 2 lambda) * max(1, |thr|) per logit (the guidance mix amplifies an
+        LM-head error by 1 + 2 lambda), tol_mass per mass."""
         cfg = self.cfg
         plan = []
         for b in range(cfg.B):
@@ -174,8 +188,15 @@ class ScdOracle:
             for s in range(Lw):
                 z = np.asarray(z_rows[b][s], dtype=np.float32)
                 thr = lg.topk_threshold(z, cfg.top_k)
-                tol_z = self.tol * max(1.0, abs(float(thr))) * (1.0 + 2.0 * cfg.cfg_lambda) \
-                    if np.isfinite(thr) else 0.0
+                if logit_err is not None:
+                    err = float(logit_err[b][s])
+                    tol_z = 2.0 * err
+                    tol_mass = self.tol_mass + 2.0 * err
+                else:
+                    err = None
+                    tol_z = self.tol * max(1.0, abs(float(thr))) * (1.0 + 2.0 * cfg.cfg_lambda) \
+                        if np.isfinite(thr) else 0.0
+                    tol_mass = self.tol_mass
                 amb = _ambiguous_ids(z, thr, cfg.top_k, tol_z)
                 keep = z >= thr
                 ov = (keep_override or {}).get((b, i + s))
@@ -185,12 +206,13 @@ class ScdOracle:
                             keep[v] = kv
                 if 0.0 < cfg.top_p < 1.0:
                     thr_p = lg.nucleus_threshold(z, keep, cfg.top_p)
-                    amb_p = _ambiguous_nucleus_ids(z, keep, cfg.top_p, self.tol_mass)
+                    amb_p = _ambiguous_nucleus_ids(z, keep, cfg.top_p, tol_mass)
                     # ids tied with the last kept logit to within the logit tolerance: another
                     # rounding of the LM head may split the tie (same rule as at the top-k boundary)
-                    tol_zp = self.tol * max(1.0, abs(float(thr_p))) * (1.0 + 2.0 * cfg.cfg_lambda)
+                    tol_zp = tol_z if err is not None else \
+                        self.tol * max(1.0, abs(float(thr_p))) * (1.0 + 2.0 * cfg.cfg_lambda)
                     near = np.nonzero(keep & (np.abs(z.astype(np.float64) - np.float64(thr_p)) <= tol_zp))[0]
-                    if near.size > 1:
+                    if near.size > 1 and tol_zp > 0.0:
                         amb_p = np.union1d(amb_p, near)
                     keep = keep & (z >= thr_p)
                     if ov:
@@ -206,7 +228,7 @@ class ScdOracle:
                 e = np.where(keep, np.exp(z64 - m), 0.0)
                 ssum = e.sum()
                 rows.append(dict(p=e / ssum, thr=thr, lse=m + np.log(ssum),
-                                 nkept=int(keep.sum()), ambiguous=amb))
+                                 nkept=int(keep.sum()), ambiguous=amb, err=err or 0.0))
             plan.append(rows)
         return plan
 
@@ -215,7 +237,12 @@ class ScdOracle:
         """Vectorised MRS (Alg. SCD(pi_MC), the parallel-for over the window); under
         pi_GS also the Gumbel draw g of every window position (Alg. SCD(pi_GS),
         "fixed noise sampling").  Overrides force a decision and are legal only on
-        flagged draws."""
+        flagged draws.  A draw is flagged when a relative perturbation of its
+        probabilities by tol + 2 (e_p + e_q) could flip it: tol covers the other side's fp32
+        evaluation of exp and of the normaliser, e_p / e_q are the logit discrepancies
+        the rows of p and q were evaluated with (p_v = exp(z_v - lse) moves by a factor
+        within exp(+-2 e) when every logit moves by at most e).  flag_accept_strict is the
+        same test at tol alone (the |u - p/q| < 1e-5 rule as stated)."""
         cfg = self.cfg
         res = []
         for b in range(cfg.B):
@@ -230,7 +257,10 @@ class ScdOracle:
                 u = philox.uniform_scalar(cfg.seed, b, j, t, philox.STREAM_ACCEPT)
                 U_fn = lambda b=b, j=j, t=t: philox.uniform_per_vocab(
                     cfg.seed, b, j, t, philox.STREAM_RESID, cfg.n_allowed)
-                r = mrs_mod.mrs(p, q, x, u, U_fn, self.tol)
+                tol = self.tol + 2.0 * (plan[b][s]["err"] + self.qerr[b].get(j, 0.0))
+                r = mrs_mod.mrs(p, q, x, u, U_fn, tol)
+                r["flag_accept_strict"] = mrs_mod.accept_flag(r["px"], r["qx"], u, self.tol)
+                r["tol"] = tol
                 r["u"] = u
                 r["stats"] = dg.row_statistics(p, q)     # (beta, collision, sum p^2, sum q^2)
                 key = (b, j)
@@ -242,7 +272,7 @@ class ScdOracle:
                     else:
                         U = U_fn()
                         w, _ = mrs_mod.residual_race(p, q, U)
-                        r.update(y=w, k=0, flag_resid=mrs_mod.residual_flag(p, q, U, w, self.tol))
+                        r.update(y=w, k=0, flag_resid=mrs_mod.residual_flag(p, q, U, w, tol))
                 if resid_override and key in resid_override and r["k"] == 0 \
                         and resid_override[key] != r["y"]:
                     assert r["flag_resid"], "residual override on an unflagged draw"
@@ -263,7 +293,7 @@ class ScdOracle:
                                                   cfg.n_allowed)
                 if Ug is not None:
                     g, _ = gs_mod.draw(p, Ug)
-                    r["flag_gs"] = gs_mod.flag(p, Ug, g, self.tol)
+                    r["flag_gs"] = gs_mod.flag(p, Ug, g, self.tol + 2.0 * plan[b][s]["err"])
                     if gs_override and key in gs_override and gs_override[key] != g:
                         assert r["flag_gs"], "Gumbel override on an unflagged draw"
                         g = int(gs_override[key])
@@ -298,9 +328,11 @@ class ScdOracle:
                 j = i + s
                 self.X[b, j] = res[b][s]["next"]
                 self.q[b][j] = plan[b][s]["p"]
+                self.qerr[b][j] = plan[b][s]["err"]
                 self.age[b, j] += 1
             for s in range(a):                        # retired positions
                 self.q[b].pop(i + s, None)
+                self.qerr[b].pop(i + s, None)
             for j in range(i + Lw, min(i + a + cfg.L, cfg.N)):   # entering positions
                 self._init_position(b, j)
             multi = []

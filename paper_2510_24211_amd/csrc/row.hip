@@ -1,10 +1,10 @@
 // Per-row part of the SCD step: top-k threshold, softmax normaliser, Modified
 // Rejection Sampling (accept test + residual resample) and -- through a
 // last-arriver ticket per sequence -- first rejection, emission and window
-// slide.  (Alg. 1; Sec. 4.3 "vectorizing verification loop without break and
-// saving the index where the first rejection occurs"; appendix "Algorithms",
-// Alg. SCD(pi_MC); top-k / temperature from the appendix "Experimental
-// Details".)
+// slide.  (Alg. 1; Sec. 4.3 "Implementation Details": every window position is
+// verified, none is skipped after a rejection, and only the offset of the first
+// rejection is kept; appendix "Algorithms", Alg. SCD(pi_MC); top-k / temperature
+// from the appendix "Experimental Details".)
 //
 //   thr  = K-th largest z (exact),  kept = { v : z_v >= thr }
 //   lse  = m + log sum_kept exp(z_v - m),  p_v = [z_v >= thr] exp(z_v - lse)
@@ -1399,11 +1399,18 @@ __global__ __launch_bounds__(THREADS) void row_kernel(const int32_t* const pos_,
 
   // ---- last workgroup of the sequence: first rejection, emit, slide -----------
   // Hand-off between workgroups WITHOUT an agent-scope fence (on this chip such a fence
-  // writes back the whole L2 and costs tens of microseconds per launch): the few bytes
-  // that travel (y, k) are stored with agent-scope atomic stores, which go straight to
-  // the device-coherent level; the wavefront waits for their completion (workgroup-scope
-  // release = s_waitcnt) before it bumps the ticket with an agent-scope atomic; the last
-  // arriver reads them back with agent-scope atomic loads.
+  // writes back the whole L2 and costs tens of microseconds per launch).  The few bytes that
+  // travel (y, k, g) are stored with agent-scope atomic stores, which are written through
+  // to the device-coherent level.  The storing wavefront then WAITS until those stores have
+  // been acknowledged (s_waitcnt vmcnt(0): the vector-memory counter of a wavefront covers
+  // its stores on gfx950) and only then bumps the sequence's ticket with an agent-scope
+  // atomic; a workgroup-scope fence alone does not make the compiler emit that wait.  The
+  // last arriver (the one that reads live - 1 from the ticket) reads y, k, g back with
+  // agent-scope atomic loads, which bypass the non-coherent cache levels.
+  // Assumption about gfx950 stated here on purpose: an agent-scope atomic store is complete
+  // at the device-coherent level when the issuing wavefront's vmcnt reaches zero, and
+  // agent-scope atomic RMWs on one address are totally ordered, so every store of a row that
+  // took an earlier ticket is visible to the workgroup that takes the last one.
   const int b = R.b, p0 = R.p0, live = R.live;
   if (tid == 0) {
     __hip_atomic_store(&a.y[R.widx], y_out, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -1411,12 +1418,13 @@ __global__ __launch_bounds__(THREADS) void row_kernel(const int32_t* const pos_,
     if (GS) __hip_atomic_store(&a.g[R.widx], g_out, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     if (a.px) a.px[R.widx] = out.px;
     if (a.qx) a.qx[R.widx] = out.qx;
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");      // the stores above have completed
     sm.last = __hip_atomic_fetch_add(&a.ticket[b], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == live - 1;
     sm.first_rej = live;
   }
   __syncthreads();
   if (!sm.last) return;
+  // nothing below may be moved above the ticket read (the barrier orders the other threads)
   __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
   int yy = -1, gg = -1;
   if (tid < live) {
@@ -1504,7 +1512,7 @@ size_t row_candidate_bytes(int rows) {
   return static_cast<size_t>(rows) * kListCap * sizeof(uint2) + 2 * small_block(rows);
 }
 
-hipError_t launch_row(const RowArgs& a_in, hipStream_t s) {
+hipError_t launch_row(const RowArgs& a_in, hipStream_t s, size_t* lds_configured) {
   if (a_in.rows <= 0) return hipSuccess;
   RowArgs a = a_in;
   const bool filter = a.top_k > 0 && a.top_k < a.n;
@@ -1530,24 +1538,22 @@ hipError_t launch_row(const RowArgs& a_in, hipStream_t s) {
     if (hipError_t e = hipGetLastError(); e != hipSuccess) return e;
   }
   const size_t lds = lds_bytes_for(a.n);
-  // the attribute belongs to the function ON A DEVICE: remembered per device.  Grows
-  // monotonically; benign if raced (the call is idempotent).
-  constexpr int kMaxDevices = 64;
-  static size_t configured_on[kMaxDevices] = {};
-  int dev = 0;
-  if (hipError_t e = hipGetDevice(&dev); e != hipSuccess) return e;
+  // The dynamic-LDS limit is an attribute of the function on a device.  Every context asks
+  // for the same value, the largest any row needs, once (a context has one stream, hence one
+  // device), so contexts of different row lengths cannot lower each other's limit.
   size_t none = 0;
-  size_t& configured = (dev >= 0 && dev < kMaxDevices) ? configured_on[dev] : none;
-  if (lds > configured) {
+  size_t& configured = lds_configured ? *lds_configured : none;
+  if (configured == 0) {
+    const size_t most = lds_bytes_for(kRowKernelMaxN);
     for (const void* f : {reinterpret_cast<const void*>(row_kernel<false, false>),
                           reinterpret_cast<const void*>(row_kernel<true, false>),
                           reinterpret_cast<const void*>(row_kernel<false, true>),
                           reinterpret_cast<const void*>(row_kernel<true, true>)}) {
       hipError_t e = hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                         static_cast<int>(lds));
+                                         static_cast<int>(most));
       if (e != hipSuccess) return e;
     }
-    configured = lds;
+    configured = most;
   }
   const bool gs = (a.gumbel || a.alpha < 1.0f) && a.g && a.mode != kRowSelectOnly;
   const bool topp = a.top_p24 != 0u || a.diag != nullptr;   // the instances with the optional parts

@@ -122,7 +122,9 @@ struct RowArgs {
   uint32_t* cand_cut;    // set by launch_row
 };
 size_t row_candidate_bytes(int rows);
-hipError_t launch_row(const RowArgs& a, hipStream_t s);
+// lds_configured: the caller's record (one per context, initially 0) that the dynamic-LDS limit of
+// the row kernels has been set on its device; null => set it on every launch
+hipError_t launch_row(const RowArgs& a, hipStream_t s, size_t* lds_configured);
 
 // ---- first rejection, emit, slide -----------------------------------------
 struct CommitArgs {
