@@ -35,7 +35,8 @@
  *     library allocates no device memory, frees nothing of the caller's and
  *     never synchronises the stream (scd_status is the one exception).
  *   - Every call returns SCD_OK (0) or a negative scd_error.  No exceptions,
- *     no errno, no global state.  Kernels are launched asynchronously on the
+ *     no errno, no global state (the one exception: the library remembers, per
+ *     GPU, the address of the static scratch of scd_couple_draft_static).  Kernels are launched asynchronously on the
  *     HIP stream given to scd_create.
  *   - A context is not thread-safe; distinct contexts are independent.
  *   - "Allowed ids" A = [v_lo, v_hi), n = |A|.  Tokens in x / y / the state are
@@ -106,7 +107,9 @@ typedef enum scd_error {
   SCD_EWORKSPACE = -2,   /* workspace pointer null / misaligned / too small      */
   SCD_EHIP = -3,         /* a HIP runtime call or kernel launch failed           */
   SCD_ENUMERIC = -4,     /* a logit row had no finite value or a NaN (scd_status) */
-  SCD_EUNSUPPORTED = -5  /* valid request this build does not implement          */
+  SCD_EUNSUPPORTED = -5, /* valid request this build does not implement          */
+  SCD_ESCRATCH = -6      /* scd_couple_draft_static: the configuration needs more than
+                            SCD_STATIC_SCRATCH_BYTES of scratch                   */
 } scd_error;
 
 /* Fields of the device-resident decode state, for scd_state_field. */
@@ -200,6 +203,25 @@ int scd_select(scd_ctx* ctx, const float* d_z, int32_t rows, float* d_thr, float
 int scd_couple_draft(scd_ctx* ctx, const float* d_z_cur, const float* d_z_prev,
                      const int32_t* d_x, const uint8_t* d_fresh, const int32_t* d_pos0,
                      int32_t iter, int32_t* d_y, uint8_t* d_k);
+
+/* scd_couple_draft for callers that cannot allocate device memory -- code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same kernels,
+ * same results; the scratch that scd_couple_draft keeps in the context's workspace (per-row
+ * thresholds / normalisers / kept counts of both logit arrays and the slice kernel's candidate
+ * lists) lives in a static device array of SCD_STATIC_SCRATCH_BYTES inside the library instead
+ * (one copy per GPU, held until the process ends).  The call allocates and frees nothing and
+ * does not touch the context's workspace.  Returns SCD_ESCRATCH when the configuration needs
+ * more: 24 bytes per window row (B * L rows, each of the six arrays rounded up to 256 bytes),
+ * plus 49216 bytes per window row when top-k filters rows of 16385..65536 ids with
+ * top_k <= 3072 (the slice kernel's candidate lists), i.e. up to 170 such rows.
+ * All calls on one GPU share that array and it keeps the last call's contents (nothing in it has
+ * to start at zero): calls that overlap in time on one GPU -- different streams or contexts --
+ * race.  The array's address is looked up once per GPU, in scd_create when a GPU is present,
+ * else in the first call. */
+#define SCD_STATIC_SCRATCH_BYTES (8u << 20)
+int scd_couple_draft_static(scd_ctx* ctx, const float* d_z_cur, const float* d_z_prev,
+                            const int32_t* d_x, const uint8_t* d_fresh, const int32_t* d_pos0,
+                            int32_t iter, int32_t* d_y, uint8_t* d_k);
 
 /* Step 4 without the slide: first rejection per sequence, accept length and
  * emitted tokens (Alg. SCD(pi_MC), "find first rejection index").

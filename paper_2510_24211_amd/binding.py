@@ -13,7 +13,8 @@ import torch
 HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(HERE, "libscd.so")
 
-SCD_OK, SCD_EINVAL, SCD_EWORKSPACE, SCD_EHIP, SCD_ENUMERIC, SCD_EUNSUPPORTED = 0, -1, -2, -3, -4, -5
+SCD_OK, SCD_EINVAL, SCD_EWORKSPACE, SCD_EHIP, SCD_ENUMERIC, SCD_EUNSUPPORTED, SCD_ESCRATCH = 0, -1, -2, -3, -4, -5, -6
+STATIC_SCRATCH_BYTES = 8 << 20
 
 # scd_field
 (F_POS, F_ITER, F_X, F_AGE, F_OUT, F_ACCEPT, F_Y, F_K, F_PX, F_QX, F_THR, F_LSE, F_NKEPT, F_Z,
@@ -73,6 +74,7 @@ def load():
     lib.scd_lm_head.argtypes = [vp, vp, vp, vp]
     lib.scd_select.argtypes = [vp, vp, i32, vp, vp, vp]
     lib.scd_couple_draft.argtypes = [vp, vp, vp, vp, vp, vp, i32, vp, vp]
+    lib.scd_couple_draft_static.argtypes = [vp, vp, vp, vp, vp, vp, i32, vp, vp]
     lib.scd_verify.argtypes = [vp, vp, vp, vp, vp, vp]
     lib.scd_step.argtypes = [vp, vp, vp, vp]
     lib.scd_step_logits.argtypes = [vp, vp, vp]
@@ -84,7 +86,7 @@ def load():
     lib.scdw_gather_hidden.argtypes = [vp, vp, i32, i32, i32, i32, i32, i32, vp, vp, vp]
     lib.scdw_copy.argtypes = [vp, vp, vp, sz]
     for name in ("scd_create", "scd_destroy", "scd_reset", "scd_state_field", "scd_lm_head",
-                 "scd_select", "scd_couple_draft", "scd_verify", "scd_step", "scd_step_logits",
+                 "scd_select", "scd_couple_draft", "scd_couple_draft_static", "scd_verify", "scd_step", "scd_step_logits",
                  "scd_set_lm_head_events", "scd_lm_head_kernel_name",
                  "scd_status", "scdw_gather_hidden", "scdw_copy"):
         getattr(lib, name).restype = ctypes.c_int
@@ -198,6 +200,17 @@ class Scd:
             self.ctx, _ptr(z, (torch.float32,), rows * self.n, "z"), rows,
             _ptr(thr, (torch.float32,), rows, "thr"), _ptr(lse, (torch.float32,), rows, "lse"),
             _ptr(nkept, (torch.int32,), rows, "nkept")), "scd_select")
+
+    def couple_draft_static(self, z_cur, z_prev, x, fresh, pos0, it, y, k):
+        """scd_couple_draft with its scratch in the library's static device array."""
+        c = self.cfg
+        r = c.B * c.L
+        self._check(self.lib.scd_couple_draft_static(
+            self.ctx, _ptr(z_cur, (torch.float32,), r * self.n, "z_cur"),
+            _ptr(z_prev, (torch.float32,), r * self.n, "z_prev"),
+            _ptr(x, (torch.int32,), r, "x"), _ptr(fresh, (torch.uint8,), r, "fresh"),
+            _ptr(pos0, (torch.int32,), c.B, "pos0"), int(it),
+            _ptr(y, (torch.int32,), r, "y"), _ptr(k, (torch.uint8,), r, "k")), "scd_couple_draft_static")
 
     def couple_draft(self, z_cur, z_prev, x, fresh, pos0, it, y, k):
         c = self.cfg

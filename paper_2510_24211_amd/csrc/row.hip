@@ -1512,13 +1512,17 @@ size_t row_candidate_bytes(int rows) {
   return static_cast<size_t>(rows) * kListCap * sizeof(uint2) + 2 * small_block(rows);
 }
 
+bool row_uses_candidates(int n, int top_k) {
+  const bool filter = top_k > 0 && top_k < n;
+  return n > kDirectMaxN && n <= kRowKernelMaxN && filter && top_k <= kListCap / 2;
+}
+
 hipError_t launch_row(const RowArgs& a_in, hipStream_t s, size_t* lds_configured) {
   if (a_in.rows <= 0) return hipSuccess;
   RowArgs a = a_in;
-  const bool filter = a.top_k > 0 && a.top_k < a.n;
   int P = 0, capE = 0;
   a.cand = nullptr;
-  if (a.n > kDirectMaxN && filter && a.cand_base && a.top_k <= kListCap / 2) {
+  if (a.cand_base && row_uses_candidates(a.n, a.top_k)) {
     P = (a.n + kSliceMax - 1) / kSliceMax;                     // <= 8 for n <= 65536
     capE = kListCap / P;
     int rank = (2 * a.top_k + P - 1) / P;

@@ -4,6 +4,7 @@
 // except scd_status.
 #include "../../include/scd.h"
 
+#include <atomic>
 #include <cmath>
 #include <cstring>
 #include <new>
@@ -92,6 +93,31 @@ size_t small_need(const scd_config& c) {
 // ... followed by the per-row candidate scratch of the slice kernel.
 size_t workspace_need(const scd_config& c) {
   return small_need(c) + align_up(scd::row_candidate_bytes(c.B * c.L));
+}
+
+// ---- scratch of the entry point that allocates nothing -----------------------------------
+// scd_couple_draft_static keeps what scd_couple_draft keeps in the caller's workspace (the
+// thresholds / normalisers / kept counts of its two logit arrays and the candidate lists of the
+// slice kernel) in this array.  Every GPU the library runs on holds its own copy at its own
+// address until the process ends; `scratch` itself is only the host-side name of the symbol, so
+// host code uses the per-device address that hipGetSymbolAddress returned, never the name.
+__device__ __align__(256) unsigned char scratch[SCD_STATIC_SCRATCH_BYTES];
+constexpr int kMaxDevices = 64;
+std::atomic<void*> g_scratch_ptr[kMaxDevices];      // device address of `scratch` per device
+
+// Address of the current device's copy; looked up once per device (racing threads store the
+// same value).  Allocates nothing.
+int static_scratch(void** out) {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess) return SCD_EHIP;
+  if (dev < 0 || dev >= kMaxDevices) return SCD_EUNSUPPORTED;
+  void* p = g_scratch_ptr[dev].load(std::memory_order_acquire);
+  if (!p) {
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return SCD_EHIP;
+    g_scratch_ptr[dev].store(p, std::memory_order_release);
+  }
+  *out = p;
+  return SCD_OK;
 }
 
 }  // namespace
@@ -245,6 +271,12 @@ int scd_create(scd_ctx** out, const scd_config* cfg, void* d_workspace, size_t w
   c->ev_start = nullptr;
   c->ev_stop = nullptr;
   c->row_lds = 0;
+  // Set-up for scd_couple_draft_static: look the scratch address of the current device up now,
+  // outside any stream capture.  Best effort (a host without a GPU can still create a context to
+  // query layouts); the entry point repeats the lookup if it is still missing.
+  void* unused = nullptr;
+  (void)static_scratch(&unused);
+  (void)hipGetLastError();
   *out = c;
   return SCD_OK;
 }
@@ -294,8 +326,14 @@ int scd_lm_head(scd_ctx* c, const uint16_t* d_h, const uint16_t* d_W, float* d_z
   return hip_rc(scd::launch_lm_head(a, c->stream));
 }
 
-int scd_select(scd_ctx* c, const float* d_z, int32_t rows, float* d_thr, float* d_lse,
-               int32_t* d_nkept) {
+}  // extern "C"
+
+namespace {
+
+// scd_select with the candidate scratch at `ws` (layout of the workspace: small_need bytes of
+// per-row scalars, then the candidate lists)
+int select_impl(scd_ctx* c, char* ws, const float* d_z, int32_t rows, float* d_thr, float* d_lse,
+                int32_t* d_nkept) {
   if (!c || !d_z || rows < 0 || !d_thr || !d_lse || !d_nkept) return SCD_EINVAL;
   if (c->n <= scd::kRowKernelMaxN) {
     scd::RowArgs ra{};
@@ -305,7 +343,7 @@ int scd_select(scd_ctx* c, const float* d_z, int32_t rows, float* d_thr, float* 
     ra.rows = rows;
     ra.B = c->cfg.B; ra.L = c->cfg.L; ra.N = c->cfg.N; ra.n = c->n; ra.top_k = c->cfg.top_k;
     ra.top_p24 = top_p24_of(c->cfg);
-    if (rows <= c->cfg.B * c->cfg.L) ra.cand_base = static_cast<char*>(c->ws) + small_need(c->cfg);
+    if (rows <= c->cfg.B * c->cfg.L) ra.cand_base = ws + small_need(c->cfg);
     return hip_rc(scd::launch_row(ra, c->stream, &c->row_lds));
   }
   scd::SelectArgs a{};
@@ -315,21 +353,20 @@ int scd_select(scd_ctx* c, const float* d_z, int32_t rows, float* d_thr, float* 
   return hip_rc(scd::launch_select(a, c->stream));
 }
 
-int scd_couple_draft(scd_ctx* c, const float* d_z_cur, const float* d_z_prev, const int32_t* d_x,
-                     const uint8_t* d_fresh, const int32_t* d_pos0, int32_t iter, int32_t* d_y,
-                     uint8_t* d_k) {
+int couple_draft_impl(scd_ctx* c, char* w, const float* d_z_cur, const float* d_z_prev,
+                      const int32_t* d_x, const uint8_t* d_fresh, const int32_t* d_pos0, int32_t iter,
+                      int32_t* d_y, uint8_t* d_k) {
   if (!c || !d_z_cur || !d_z_prev || !d_x || !d_pos0 || !d_y || !d_k || iter < 0)
     return SCD_EINVAL;
   const int rows = c->cfg.B * c->cfg.L;
   const size_t seg = align_up(4 * static_cast<size_t>(rows));
-  char* w = static_cast<char*>(c->ws);
   float* thr_c = reinterpret_cast<float*>(w);
   float* lse_c = reinterpret_cast<float*>(w + seg);
   int32_t* nk_c = reinterpret_cast<int32_t*>(w + 2 * seg);
   float* thr_p = reinterpret_cast<float*>(w + 3 * seg);
   float* lse_p = reinterpret_cast<float*>(w + 4 * seg);
   int32_t* nk_p = reinterpret_cast<int32_t*>(w + 5 * seg);
-  if (int rc = scd_select(c, d_z_prev, rows, thr_p, lse_p, nk_p); rc != SCD_OK) return rc;
+  if (int rc = select_impl(c, w, d_z_prev, rows, thr_p, lse_p, nk_p); rc != SCD_OK) return rc;
   if (c->n <= scd::kRowKernelMaxN) {
     scd::RowArgs ra{};
     ra.alpha = 1.0f;
@@ -344,10 +381,10 @@ int scd_couple_draft(scd_ctx* c, const float* d_z_cur, const float* d_z_prev, co
     ra.B = c->cfg.B; ra.L = c->cfg.L; ra.N = c->cfg.N; ra.n = c->n; ra.top_k = c->cfg.top_k;
     ra.top_p24 = top_p24_of(c->cfg);
     ra.v_lo = c->cfg.v_lo; ra.seed = c->cfg.seed;
-    ra.cand_base = static_cast<char*>(c->ws) + small_need(c->cfg);
+    ra.cand_base = w + small_need(c->cfg);
     return hip_rc(scd::launch_row(ra, c->stream, &c->row_lds));
   }
-  if (int rc = scd_select(c, d_z_cur, rows, thr_c, lse_c, nk_c); rc != SCD_OK) return rc;
+  if (int rc = select_impl(c, w, d_z_cur, rows, thr_c, lse_c, nk_c); rc != SCD_OK) return rc;
   scd::MrsArgs a{};
   a.z_cur = d_z_cur; a.z_prev = d_z_prev;
   a.thr_cur = thr_c; a.lse_cur = lse_c; a.thr_prev = thr_p; a.lse_prev = lse_p;
@@ -356,6 +393,41 @@ int scd_couple_draft(scd_ctx* c, const float* d_z_cur, const float* d_z_prev, co
   a.y = d_y; a.k = d_k;
   a.B = c->cfg.B; a.L = c->cfg.L; a.N = c->cfg.N; a.n = c->n; a.seed = c->cfg.seed;
   return hip_rc(scd::launch_mrs(a, c->stream));
+}
+
+}  // namespace
+
+extern "C" {
+
+int scd_select(scd_ctx* c, const float* d_z, int32_t rows, float* d_thr, float* d_lse,
+               int32_t* d_nkept) {
+  if (!c) return SCD_EINVAL;
+  return select_impl(c, static_cast<char*>(c->ws), d_z, rows, d_thr, d_lse, d_nkept);
+}
+
+int scd_couple_draft(scd_ctx* c, const float* d_z_cur, const float* d_z_prev, const int32_t* d_x,
+                     const uint8_t* d_fresh, const int32_t* d_pos0, int32_t iter, int32_t* d_y,
+                     uint8_t* d_k) {
+  if (!c) return SCD_EINVAL;
+  return couple_draft_impl(c, static_cast<char*>(c->ws), d_z_cur, d_z_prev, d_x, d_fresh, d_pos0, iter,
+                           d_y, d_k);
+}
+
+int scd_couple_draft_static(scd_ctx* c, const float* d_z_cur, const float* d_z_prev, const int32_t* d_x,
+                            const uint8_t* d_fresh, const int32_t* d_pos0, int32_t iter, int32_t* d_y,
+                            uint8_t* d_k) {
+  if (!c) return SCD_EINVAL;
+  // what this configuration really uses of the workspace layout: the per-row scalars, and the
+  // candidate lists only when its rows go through the slice kernel
+  const bool cands = scd::row_uses_candidates(c->n, c->cfg.top_k);
+  const size_t need = small_need(c->cfg) + (cands ? align_up(scd::row_candidate_bytes(c->cfg.B * c->cfg.L)) : 0);
+  if (need > static_cast<size_t>(SCD_STATIC_SCRATCH_BYTES)) return SCD_ESCRATCH;
+  void* base = nullptr;
+  if (int rc = static_scratch(&base); rc != SCD_OK) return rc;
+  // nothing in the scratch has to start at zero: the per-row scalars and, for every live row,
+  // all slice counts / cuts the row kernel reads are written by the launches of this call first
+  return couple_draft_impl(c, static_cast<char*>(base), d_z_cur, d_z_prev, d_x, d_fresh, d_pos0, iter,
+                           d_y, d_k);
 }
 
 int scd_verify(scd_ctx* c, const uint8_t* d_k, const int32_t* d_y, const int32_t* d_pos0,
@@ -460,6 +532,8 @@ const char* scd_strerror(int code) {
     case SCD_EHIP: return "HIP runtime call or kernel launch failed";
     case SCD_ENUMERIC: return "a logit row had no finite value or contained NaN";
     case SCD_EUNSUPPORTED: return "not implemented in this build";
+    case SCD_ESCRATCH:
+      return "configuration needs more scratch than the library's static array (SCD_STATIC_SCRATCH_BYTES)";
     default: return "unknown error code";
   }
 }

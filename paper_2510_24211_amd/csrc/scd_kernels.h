@@ -122,6 +122,8 @@ struct RowArgs {
   uint32_t* cand_cut;    // set by launch_row
 };
 size_t row_candidate_bytes(int rows);
+// whether launch_row, given scratch, runs the slice kernel for rows of n ids under this top-k
+bool row_uses_candidates(int n, int top_k);
 // lds_configured: the caller's record (one per context, initially 0) that the dynamic-LDS limit of
 // the row kernels has been set on its device; null => set it on every launch
 hipError_t launch_row(const RowArgs& a, hipStream_t s, size_t* lds_configured);
