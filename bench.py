@@ -8,15 +8,19 @@ windows.  The windows' hidden states (which depend on the decode state) are
 assembled for every step by an untimed recording decode, so all inputs are
 resident in HBM before the timed region starts; nothing crosses PCIe inside it.
 
-Prints ONE JSON line.  `value` = window positions verified per second over the
-timed steps; `tokens_per_s` = emitted tokens per second over the same steps.
-`roofline` describes the dominant kernel (the LM-head stream over W), timed with
-HIP events attached to the LM-head dispatch inside scd_step (they take the kernel's own
-start and stop time on the stream it runs on), in a repeat of the timed steps (a step
-launched that way is about a microsecond slower, so `value`
-comes from the pass without them; `config.ms_per_step_with_events` is the other).  `cpu_baseline`
-is the NumPy oracle timed on the host cores on a bounded sample of the same
-workload.
+Prints ONE JSON line.  The top level is the full-vocabulary workload (C2-fullV: every one of
+the V = 65536 ids allowed, the stream the ">= 70 % of HBM" target is stated on): `value` =
+window positions verified per second, `tokens_per_s` = emitted tokens per second, both from the
+MEDIAN of `repeats` timed passes of exactly `steps` steps each (the passes continue one decode
+after `warmup` untimed steps; `ms_per_step_min` / `_max` give the spread).  `roofline` describes
+the dominant kernel (the LM-head stream over W), timed with HIP events attached to the LM-head
+dispatch inside scd_step (they take the kernel's own start and stop time on the stream it runs
+on) in one more identical pass (a step launched that way is about a microsecond slower, so
+`value` never comes from it); `roofline.step_frac` is the whole step against the same peak:
+algorithmic step bytes / median step time / 8 TB/s.  `companions` holds the same measurement of
+the other workloads (C2 as specified = 8192 allowed ids, C1, C3, C4) with the same --steps /
+--warmup / --repeats.  `cpu_baseline` is the NumPy oracle timed on the host cores on a bounded
+sample of the top-level workload, with the number of draws it flags as numerically fragile.
 """
 import argparse
 import ctypes
@@ -38,8 +42,14 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=0, help="timed steps; 0 = one whole decode")
     ap.add_argument("--warmup", type=int, default=0, help="untimed steps; 0 = one whole decode")
-    ap.add_argument("--workload", default="C2",
-                    help="C1 | C2 | C2-fullV | C3 | C4 (see paper_2510_24211_amd/workload.py)")
+    ap.add_argument("--workload", default=None,
+                    help="C1 | C2 | C2-fullV | C3 | C4 | C4-topp (see paper_2510_24211_amd/workload.py): "
+                         "measure this workload alone.  Default: C2-fullV at the top level and "
+                         "C2, C1, C3, C4 as `companions`")
+    ap.add_argument("--repeats", type=int, default=5,
+                    help="timed passes of --steps steps each; value = their median (default 5)")
+    ap.add_argument("--no-companions", action="store_true",
+                    help="default run only: skip the companion workloads")
     ap.add_argument("--diagnostics", action="store_true",
                     help="also compute the per-position statistics in every step (config.diagnostics) "
                          "and report their means over the recorded decode")
@@ -55,11 +65,6 @@ def parse():
                          "iterations from a fresh state (both must be given and fit in one decode)")
     ap.add_argument("--no-events", action="store_true",
                     help="do not record the per-step LM-head events (no roofline object)")
-    ap.add_argument("--events-in-step", action="store_true",
-                    help="record the LM-head events in the pass that gives `value` (default: in an "
-                         "identical second pass, because the events slow the step down)")
-    ap.add_argument("--no-full-vocab", action="store_true",
-                    help="C2 only: skip the companion measurement with all 65536 ids allowed")
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="MIB",
                     help="profiling aid: run 20 launches of the library's plain copy kernel over MIB "
                          "MiB and exit (scales a profiler's HBM byte counters)")
@@ -100,7 +105,11 @@ class HipEvents:
 
 def cpu_baseline(w, seconds, coupling="mc", sjd_mix=0.0):
     """The oracle as it stands, on the host cores, for about `seconds` (whole decodes are
-    repeated until the time is up; the last one may be cut short)."""
+    repeated until the time is up; the last one may be cut short).  Also counts the draws the
+    oracle flags as numerically fragile on that sample (its a-priori bands: |u - p/q| < 1e-5, a
+    residual race that a 1e-5 relative perturbation could flip, a top-k boundary with another
+    logit within 1e-5 (1 + 2 lambda) max(1, |thr|)): the draws on which a second implementation
+    is allowed to decide differently."""
     import numpy as np
     from oracle import logits as lg
     from oracle import scd as oscd
@@ -121,6 +130,7 @@ def cpu_baseline(w, seconds, coupling="mc", sjd_mix=0.0):
     tab.window(list(o.i), [[0] * w.L for _ in range(w.B)])      # warm the generator caches
     t_in = 0.0
     steps = positions = tokens = decodes = 0
+    flagged = dict(draws=0, accept=0, residual=0, topk_rows=0)
     t0 = time.perf_counter()
     while time.perf_counter() - t0 - t_in < seconds:
         if o.done():
@@ -142,7 +152,15 @@ def cpu_baseline(w, seconds, coupling="mc", sjd_mix=0.0):
             c = lg.lm_head(h[b, 0, :Lw], W64)
             u = lg.lm_head(h[b, 1, :Lw], W64) if w.C == 2 else None
             z_rows.append(lg.process_logits(c, u, w.cfg_lambda, w.temperature))
-        o.step(z_rows)
+        plan, res, _ = o.step(z_rows)
+        ti = time.perf_counter()                  # reading the flags off is not the method either
+        for rows_p, rows_r in zip(plan, res):
+            for rp, rr in zip(rows_p, rows_r):
+                flagged["draws"] += 1
+                flagged["accept"] += int(rr["flag_accept_strict"])
+                flagged["residual"] += int(rr["flag_resid"])
+                flagged["topk_rows"] += int(len(rp["ambiguous"]) > 0)
+        t_in += time.perf_counter() - ti
         steps += 1
     T = time.perf_counter() - t0 - t_in
     positions += o.positions_verified
@@ -150,7 +168,14 @@ def cpu_baseline(w, seconds, coupling="mc", sjd_mix=0.0):
     return {"value": positions / T, "unit": "positions/s", "cores": int(threads),
             "kind": "oracle", "tokens_per_s": float(tokens) / T,
             "sample": f"{steps} iterations of {w.name} ({decodes} whole decodes and the start of the "
-                      f"next; {positions} window positions, {tokens} tokens) in {T:.1f} s, NumPy fp64"}
+                      f"next; {positions} window positions, {tokens} tokens) in {T:.1f} s, NumPy fp64",
+            "flagged_draws": flagged}
+
+
+COMPANIONS = ("C2", "C1", "C3", "C4")
+# what a companion object keeps of a workload's result
+COMPANION_KEYS = ("value", "unit", "tokens_per_s", "steps", "warmup", "repeats", "ms_per_step",
+                  "ms_per_step_min", "ms_per_step_max", "config", "roofline")
 
 
 def main():
@@ -177,14 +202,17 @@ def main():
                           "bytes_written_per_launch": nbytes}))
         return
 
-    out, w = measure(a, a.workload, inputs := {})
-    if a.workload == "C2" and not a.quick and not a.no_full_vocab:
-        # the same step with every one of the V = 65536 ids allowed (LM head streams all of W)
-        fv, _ = measure(a, "C2-fullV", inputs)
-        out["full_vocab_variant"] = {k: fv[k] for k in ("value", "unit", "tokens_per_s", "steps",
-                                                         "ms_per_step", "config", "roofline")}
+    top = a.workload or "C2-fullV"
+    out, w = measure(a, top, inputs := {})
+    if a.workload is None and not a.quick and not a.no_companions:
+        out["companions"] = {}
+        for name in COMPANIONS:
+            print(f"bench.py: companion workload {name}", file=sys.stderr, flush=True)
+            r, _ = measure(a, name, inputs)
+            out["companions"][name] = {k: r[k] for k in COMPANION_KEYS}
     inputs.clear()
     if not a.no_cpu_baseline:
+        print("bench.py: CPU oracle baseline", file=sys.stderr, flush=True)
         out["cpu_baseline"] = cpu_baseline(w, a.cpu_seconds, a.coupling, a.sjd_mix)
     print(json.dumps(out))
 
@@ -208,6 +236,7 @@ def measure(a, name, inputs):
     key = (w.V, w.d, w.B, w.C, w.N, w.age_cap, w.seed, w.decay, w.frames)
     if inputs.get("key") != key:
         inputs.clear()
+        torch.cuda.empty_cache()
         inputs.update(key=key, W=to_dev(wl.lm_head_weight(w)), table=to_dev(wl.HiddenTable(w).full()))
     W, table = inputs["W"], inputs["table"]
     cfg = B.config_from_workload(w)
@@ -216,15 +245,16 @@ def measure(a, name, inputs):
     cfg.diagnostics = int(a.diagnostics)
     s = B.Scd(cfg, dev)
     st = s.alloc_state()
-    h = torch.empty((w.B, w.C, w.L, w.d), dtype=torch.bfloat16, device=dev)
     t_setup = time.perf_counter() - t_setup
 
-    # ---- recording pass (untimed; also the warm-up) ------------------------------------
+    # ---- recording pass (untimed; also the warm-up of the caches) -------------------------
     # The hidden states of a step depend on the decode state (window start and ages), which
     # lives on the device.  One untimed decode assembles every step's [B, C, L, d] input with
     # the device-side gather and keeps it, so that the timed steps below find their inputs
     # resident in HBM and consist of scd_step alone.  The trajectory is deterministic (same
-    # seed, same kernels), which the token comparison after the timed pass confirms.
+    # seed, same kernels), which the comparison of the window starts after every timed pass
+    # confirms.  Per recorded step it also keeps the running totals of verified positions and
+    # emitted tokens, from which the work of any range of steps follows.
     CH = 64
     chunks = []
 
@@ -235,6 +265,8 @@ def measure(a, name, inputs):
 
     diag_sum = torch.zeros(4, dtype=torch.float64, device=dev)     # beta, C, bound, live rows
     hamm_sum = torch.zeros(6, dtype=torch.int64, device=dev)       # (differing, compared) for 1, 2, 3 iterations apart
+    totals = []                                                    # per step: [verified, tokens] so far (device)
+    pos_after = []                                                 # per step: window starts after it (device)
 
     def record(limit):
         """Decode from a fresh state, at most `limit` steps; returns the iteration count."""
@@ -245,6 +277,9 @@ def measure(a, name, inputs):
                 hi = h_of(i)
                 s.gather_hidden(table, w.age_cap, st, hi)
                 s.step(hi, W, st)
+                pos = s.state_field(st, B.F_POS)
+                totals.append(torch.stack([s.state_field(st, B.F_VERIFIED).sum(), pos.sum()]))
+                pos_after.append(pos.clone())
                 if a.diagnostics:                 # rows that are not live hold zeros
                     d = s.state_field(st, B.F_DIAG).view(-1, 4).double()
                     diag_sum[0] += d[:, 0].sum()
@@ -259,131 +294,132 @@ def measure(a, name, inputs):
                 return flags[2]
         return i
 
+    R = max(1, a.repeats)
     if a.quick:
         assert a.steps > 0 and a.warmup > 0, "--quick needs --steps and --warmup"
-        nfe = record(a.steps + a.warmup)          # the decode may end earlier: then steps wrap
-        verified_per_decode = int(s.state_field(st, B.F_VERIFIED).sum().item())
+        nfe = record(a.warmup + (R + 1) * a.steps)   # the decode may end earlier: then steps wrap
     else:
         nfe = record(1 << 30)                     # whole decode
-        verified_per_decode = int(s.state_field(st, B.F_VERIFIED).sum().item())
-    tokens_ref = s.state_field(st, B.F_OUT).clone()
+    tot = torch.stack(totals[:nfe]).cpu().numpy().astype(np.int64)       # [nfe, 2] cumulative
+    per_step = np.diff(np.concatenate([np.zeros((1, 2), dtype=np.int64), tot]), axis=0)
+    whole = not a.quick
     K = a.steps if a.steps > 0 else nfe
     Wm = a.warmup
-    first = 0                                     # recorded step the timed pass starts at
-    s.reset(st)
-    if Wm > 0:
-        for i in range(Wm):
-            if first == nfe:
-                s.reset(st)
-                first = 0
-            s.step(h_of(first), W, st)
-            first += 1
-        if not a.quick:                           # default: the timed pass starts a fresh decode
-            s.reset(st)
-            first = 0
-
-    use_events = not a.no_events
-    ev = HipEvents(K) if use_events else None
-    enqueue_us = []                               # host time per step to enqueue (first pass = value's)
-
     hs = [h_of(i) for i in range(nfe)]            # views, made outside the timed loops
 
-    def timed_pass(with_events):
-        v0 = int(s.state_field(st, B.F_VERIFIED).sum().item())   # non-zero only after --quick warm-up
-        p0 = int(s.state_field(st, B.F_POS).sum().item())
-        torch.cuda.synchronize()
-        done_decodes, in_decode = 0, first
-        t0 = time.perf_counter()
-        for i in range(K):
-            if in_decode == nfe:                  # sequence(s) finished: start the next decode
+    cursor = [0]                                  # next recorded step
+
+    def run_steps(count, with_events=None):
+        """Enqueues `count` steps that continue the decode (a finished decode is followed by a
+        fresh one); returns the recorded indices of the steps."""
+        idx = []
+        for i in range(count):
+            if cursor[0] == nfe:
                 s.reset(st)
-                done_decodes, in_decode = done_decodes + 1, 0
-            if with_events:
-                s.set_lm_head_events(*ev.pair(i))
-            s.step(hs[in_decode], W, st)
-            in_decode += 1
+                cursor[0] = 0
+            if with_events is not None:
+                s.set_lm_head_events(*with_events.pair(i))
+            s.step(hs[cursor[0]], W, st)
+            idx.append(cursor[0])
+            cursor[0] += 1
+        return idx
+
+    def check_reproduced():
+        got = s.state_field(st, B.F_POS)
+        assert torch.equal(got, pos_after[cursor[0] - 1]), "decode is not reproducible"
+
+    def timed_pass(ev=None):
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        idx = run_steps(K, ev)
         t_enq = time.perf_counter() - t0
         torch.cuda.synchronize()
         T = time.perf_counter() - t0
-        enqueue_us.append(t_enq / K * 1e6)
-        if with_events:
+        if ev is not None:
             s.set_lm_head_events(None, None)
-        verified = done_decodes * verified_per_decode - v0 + int(s.state_field(st, B.F_VERIFIED).sum().item())
-        tokens = done_decodes * w.B * w.N - p0 + int(s.state_field(st, B.F_POS).sum().item())
-        if in_decode == nfe and not a.quick:      # ended on a whole decode: same tokens as recorded
-            assert torch.equal(s.state_field(st, B.F_OUT), tokens_ref), "decode is not reproducible"
-        return T, verified, tokens
+        check_reproduced()
+        work = per_step[idx].sum(axis=0)
+        return dict(T=T, verified=int(work[0]), tokens=int(work[1]), enqueue_us=t_enq / K * 1e6)
 
+    s.reset(st)
+    if Wm > 0:
+        run_steps(Wm)
+    passes = [timed_pass() for _ in range(R)]
     # A step whose LM head carries the events is about a microsecond slower (the dispatch then
-    # reports its timestamps; recorded event PAIRS cost 2-6 us: two more packets between the
-    # kernels), so the throughput comes from a pass without them and the LM-head timing from
-    # an identical pass with them, right after (--events-in-step: one pass for both).
-    T_ev = None
-    if use_events and not a.events_in_step:
-        T, verified, tokens = timed_pass(False)
-        if a.quick:                               # the second pass repeats the same steps
-            s.reset(st)
-            redo = 0
-            for i in range(Wm):
-                if redo == nfe:
-                    s.reset(st)
-                    redo = 0
-                s.step(h_of(redo), W, st)
-                redo += 1
-        else:
-            s.reset(st)
-        T_ev, _, _ = timed_pass(True)
-    else:
-        T, verified, tokens = timed_pass(use_events)
-        T_ev = T if use_events else None
+    # reports its timestamps), so the throughput comes from the passes without them and the
+    # LM-head timing from one more identical pass with them.
+    use_events = not a.no_events
+    lm_ms = T_ev = None
+    if use_events:
+        ev = HipEvents(K)
+        T_ev = timed_pass(ev)["T"]
+        lm_ms = float(np.mean([ev.elapsed_ms(i) for i in range(K)]))
+        ev.destroy()
     rc, flags = s.status(st)
     assert rc == B.SCD_OK
 
-    lm_ms = None
-    if use_events:
-        lm_ms = float(np.mean([ev.elapsed_ms(i) for i in range(K)]))
-        ev.destroy()
+    order = sorted(range(R), key=lambda r: passes[r]["T"])
+    med = passes[order[(R - 1) // 2]]             # the median pass (lower median for an even count)
+    T = med["T"]
 
     n = w.n_allowed
     w_bytes = 2 * w.d * n
     h_bytes = 2 * w.M * w.d
     alg_bytes = w_bytes + h_bytes               # per LM-head launch (W slice once + hidden rows)
+    step_bytes = alg_bytes + 2 * w.B * w.L * min(n, w.top_k or n) * 8   # + the sparse q-state, read and written
     flops = 2.0 * w.M * w.d * n
+    resident = w_bytes <= 192 * 1024 * 1024      # the library's own rule for keeping W in the caches
+    mfma_bound = w.M > 310                       # GEMM intensity M FLOP/B against the ridge 2.5 PF / 8 TB/s
     roof = None
     if lm_ms:
         gbs = alg_bytes / (lm_ms * 1e-3) / 1e9
-        traffic = None
-        tpath = os.path.join(ROOT, "profiles", f"traffic_{w.name}.json")
-        if os.path.exists(tpath):
-            traffic = json.load(open(tpath)).get("hbm_bytes_per_launch")
-        roof = {"bound": "hbm", "achieved": gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                "frac": gbs / HBM_PEAK_GBS, "traffic": traffic, "kernel": s.lm_head_kernel_name(),
+        tfl = flops / (lm_ms * 1e-3) / 1e12
+        extra = {}
+        for tag in ("traffic", "mfma_util"):
+            tpath = os.path.join(ROOT, "profiles", f"{tag}_{w.name}.json")
+            extra[tag] = json.load(open(tpath)) if os.path.exists(tpath) else None
+        roof = {"bound": "mfma" if mfma_bound else "hbm",
+                "achieved": tfl if mfma_bound else gbs,
+                "peak": MFMA_BF16_PEAK_TFLOPS if mfma_bound else HBM_PEAK_GBS,
+                "unit": "TFLOP/s" if mfma_bound else "GB/s",
+                "frac": tfl / MFMA_BF16_PEAK_TFLOPS if mfma_bound else gbs / HBM_PEAK_GBS,
+                "traffic": (extra["traffic"] or {}).get("hbm_bytes_per_launch"),
+                "kernel": s.lm_head_kernel_name(),
                 "avg_launch_us": lm_ms * 1e3, "algorithmic_bytes_per_launch": alg_bytes,
-                "mfma_tflops": flops / (lm_ms * 1e-3) / 1e12,
-                "mfma_frac": flops / (lm_ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS}
+                "hbm_gbs": gbs, "hbm_frac": gbs / HBM_PEAK_GBS,
+                "mfma_tflops": tfl, "mfma_frac_by_time": tfl / MFMA_BF16_PEAK_TFLOPS,
+                "mfma_counters": extra["mfma_util"],
+                # the whole step against the same HBM peak: what the method must move per step
+                "step_bytes_algorithmic": step_bytes,
+                "step_frac": step_bytes / (T / K) / 1e9 / HBM_PEAK_GBS,
+                "step_us": T / K * 1e6,
+                "w_slice_cache_resident": bool(resident),
+                "note": ("the W slice (%.0f MB) stays in the 256 MB memory-side cache from step to "
+                         "step: bytes/time is a rate out of that cache, not an HBM figure" % (w_bytes / 1e6))
+                if resident else "W is streamed from HBM every step (non-temporal loads)"}
 
     out = {
         "metric": "window_positions_verified_per_s",
-        "value": verified / T,
+        "value": med["verified"] / T,
         "unit": "positions/s",
-        "tokens_per_s": tokens / T,
-        "n_gpus": 1, "steps": K, "warmup": Wm if Wm > 0 else nfe,
+        "tokens_per_s": med["tokens"] / T,
+        "n_gpus": 1, "steps": K, "warmup": Wm, "repeats": R,
         "ms_per_step": T / K * 1e3,
+        "ms_per_step_min": passes[order[0]]["T"] / K * 1e3,
+        "ms_per_step_max": passes[order[-1]]["T"] / K * 1e3,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": f"{w.name}: B={w.B} CFG={'on' if w.C == 2 else 'off'} L={w.L} "
                                f"N={w.N} V={w.V} allowed={n} d={w.d} top_k={w.top_k} top_p={w.top_p} "
                                f"lambda={w.cfg_lambda} seed={w.seed} coupling={a.coupling} sjd_mix={a.sjd_mix} "
                                f"(synthetic drift model)",
-                   "decode_iterations": None if a.quick else int(nfe),
-                   "tokens_per_iteration": None if a.quick else w.B * w.N / nfe,
-                   "step_bytes_algorithmic": alg_bytes + 2 * w.B * w.L * min(n, w.top_k or n) * 8,
-                   "step_hbm_frac": (alg_bytes + 2 * w.B * w.L * min(n, w.top_k or n) * 8)
-                   / (T / K) / 1e9 / HBM_PEAK_GBS,
-                   "lm_head_events": ("none" if not use_events else "same pass as value"
-                                      if a.events_in_step else "repeat of the timed steps"),
+                   "decode_iterations": int(nfe) if whole else None,
+                   "tokens_per_iteration": w.B * w.N / nfe if whole else None,
+                   "timed": f"{R} passes of {K} steps continuing one decode after {Wm} warm-up steps"
+                            + (" (a pass = one whole decode)" if whole and K == nfe and Wm == 0 else ""),
+                   "ms_per_step_all_passes": [p["T"] / K * 1e3 for p in passes],
                    "ms_per_step_with_events": None if T_ev is None else T_ev / K * 1e3,
-                   "host_enqueue_us_per_step": enqueue_us[0],
+                   "host_enqueue_us_per_step": med["enqueue_us"],
                    "setup_s": t_setup},
         "roofline": roof,
     }
@@ -397,6 +433,7 @@ def measure(a, name, inputs):
                               "hamming_fraction": float(hs_[0]) / max(float(hs_[1]), 1.0),
                               "hamming_fraction_2_iterations_apart": float(hs_[2]) / max(float(hs_[3]), 1.0),
                               "hamming_fraction_3_iterations_apart": float(hs_[4]) / max(float(hs_[5]), 1.0)}
+    del chunks, hs, totals, pos_after
     return out, w
 
 
