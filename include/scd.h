@@ -70,7 +70,8 @@ typedef struct scd_config {
   int32_t N;           /* tokens to generate per sequence, >= 1                     */
   int32_t V;           /* vocabulary size = rows of W                               */
   int32_t d;           /* hidden size, multiple of 8; 0 => no LM head (logits given) */
-  int32_t v_lo, v_hi;  /* allowed ids [v_lo, v_hi), 0 <= v_lo < v_hi <= V           */
+  int32_t v_lo, v_hi;  /* allowed ids [v_lo, v_hi), 0 <= v_lo < v_hi <= V;
+                          L * (v_hi - v_lo) must stay below 2^31                    */
   int32_t top_k;       /* 0 => off; K = min(top_k, n)                               */
   float temperature;   /* tau > 0                                                   */
   float cfg_lambda;    /* 0 => no guidance (C = 1); else C = 2, z = (1+l)c - l u    */
@@ -212,8 +213,8 @@ int scd_couple_draft(scd_ctx* ctx, const float* d_z_cur, const float* d_z_prev,
  * (one copy per GPU, held until the process ends).  The call allocates and frees nothing and
  * does not touch the context's workspace.  Returns SCD_ESCRATCH when the configuration needs
  * more: 24 bytes per window row (B * L rows, each of the six arrays rounded up to 256 bytes),
- * plus 49216 bytes per window row when top-k filters rows of 16385..65536 ids with
- * top_k <= 3072 (the slice kernel's candidate lists), i.e. up to 170 such rows.
+ * plus 51200 bytes per window row when top-k filters rows of 16385..65536 ids with
+ * top_k <= 3072 (the slice kernel's candidate lists), i.e. up to 163 such rows.
  * All calls on one GPU share that array and it keeps the last call's contents (nothing in it has
  * to start at zero): calls that overlap in time on one GPU -- different streams or contexts --
  * race.  The array's address is looked up once per GPU, in scd_create when a GPU is present,

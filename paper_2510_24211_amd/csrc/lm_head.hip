@@ -30,6 +30,7 @@
 //     1/KS part of k each, stage their own h tiles privately as well (no barrier in
 //     the loop), and their partial sums are added in wavefront order through LDS at
 //     the end (a fixed order: deterministic).
+#include "scd_device.h"
 #include "scd_kernels.h"
 
 #include <hip/hip_ext.h>
@@ -114,6 +115,7 @@ struct Cfg {
 struct RowBlockDst {
   float* zb;
   int b, sbase, p0, live;
+  int lmask;    // L - 1 if L is a power of two (ring slot by masking), else -1 (by division)
 };
 __device__ __forceinline__ RowBlockDst row_block_dst(const LmHeadArgs& a, int rb, int nLb) {
   RowBlockDst r;
@@ -127,37 +129,186 @@ __device__ __forceinline__ RowBlockDst row_block_dst(const LmHeadArgs& a, int rb
     r.live = min(a.L, a.N - r.p0);
   }
   if (a.iter) r.zb += static_cast<size_t>(a.iter[r.b] & 1) * a.parity_stride;
+  r.lmask = (a.L & (a.L - 1)) == 0 ? a.L - 1 : -1;
   return r;
 }
+// Ring slot of window position s (an integer division per logit otherwise: 16 of them per lane)
+__device__ __forceinline__ int ring_slot(const LmHeadArgs& a, const RowBlockDst& r, int s) {
+  if (!a.pos) return s;
+  return r.lmask >= 0 ? ((r.p0 + s) & r.lmask) : (r.p0 + s) % a.L;
+}
 
-// Guidance mix and temperature of one logit (cond sum c, uncond sum u), stored for window
-// position s and allowed id v.
+// Guidance mix and temperature of one logit (cond sum c, uncond sum u): three fp32 roundings
+// for the mix, one for the division (skipped for tau = 1, where it changes nothing).
+template <int C>
+__device__ __forceinline__ float processed_logit(const LmHeadArgs& a, float c, float u) {
+  float z = c;
+  if (C == 2) z = __fsub_rn(__fmul_rn(a.one_plus_lam, c), __fmul_rn(a.lam, u));
+  return a.tau == 1.0f ? z : __fdiv_rn(z, a.tau);
+}
+// Stores processed logit z of window position s and allowed id v.
+__device__ __forceinline__ void store_z(const LmHeadArgs& a, const RowBlockDst& r, int s, int v, float z) {
+  if (s >= r.live) return;
+  // the sequence's part of the address is uniform (scalar unit); slot * n + v fits 32 bits
+  // (L * n < 2^31 is checked when the context is created)
+  float* const zseq = r.zb + static_cast<size_t>(r.b) * a.L * a.n;
+  zseq[static_cast<uint32_t>(ring_slot(a, r, s)) * static_cast<uint32_t>(a.n) + static_cast<uint32_t>(v)] = z;
+}
 template <int C>
 __device__ __forceinline__ void store_logit(const LmHeadArgs& a, const RowBlockDst& r, int s, int v,
                                             float c, float u) {
-  if (s >= r.live) return;
-  float z = c;
-  if (C == 2) z = __fsub_rn(__fmul_rn(a.one_plus_lam, c), __fmul_rn(a.lam, u));
-  z = __fdiv_rn(z, a.tau);
-  const int slot = a.pos ? (r.p0 + s) % a.L : s;
-  r.zb[(static_cast<size_t>(r.b) * a.L + slot) * a.n + v] = z;
+  store_z(a, r, s, v, processed_logit<C>(a, c, u));
 }
 
 // Epilogue of a wavefront that holds whole sums.  Element j of lane (ln, lg) is row
-// (j/4)*8 + lg*4 + j%4, column ln of the 32x32 tile.
+// (j/4)*8 + lg*4 + j%4, column ln of the 32x32 tile.  zout takes the processed logits.
+// rbd[rbw]: where row block rb0 + rbw goes (fetched at kernel start: window start and iteration
+// parity come from memory, and the epilogue should not begin with that round trip).
 template <int RBW, int C>
-__device__ __forceinline__ void epilogue(const LmHeadArgs& a, const f32x16 (&acc)[RBW * C], int nLb,
-                                         int nRB, int rb0, int v, int lg) {
+__device__ __forceinline__ void epilogue(const LmHeadArgs& a, const f32x16 (&acc)[RBW * C], int nRB, int rb0,
+                                         const RowBlockDst (&rbd)[RBW], int v, int lg, float (&zout)[RBW][16]) {
+#pragma unroll
+  for (int rbw = 0; rbw < RBW; ++rbw)
+#pragma unroll
+    for (int j = 0; j < 16; ++j) zout[rbw][j] = processed_logit<C>(a, acc[rbw * C][j], acc[rbw * C + C - 1][j]);
   if (v >= a.n) return;
 #pragma unroll
   for (int rbw = 0; rbw < RBW; ++rbw) {
-    const int rb = rb0 + rbw;
-    if (rb >= nRB) break;
-    const RowBlockDst r = row_block_dst(a, rb, nLb);
+    if (rb0 + rbw >= nRB) break;
+    const RowBlockDst& r = rbd[rbw];
 #pragma unroll
     for (int j = 0; j < 16; ++j)
-      store_logit<C>(a, r, r.sbase + (j >> 2) * 8 + lg * 4 + (j & 3), v, acc[rbw * C][j],
-                     acc[rbw * C + C - 1][j]);
+      store_z(a, r, r.sbase + (j >> 2) * 8 + lg * 4 + (j & 3), v, zout[rbw][j]);
+  }
+}
+
+// ---- per-tile top-k candidates (first half of the top-k selection, fused into the epilogue) ----
+// A workgroup that owns 256 neighbouring columns parks its processed logits in LDS as a tile
+// zt[row][kTilePitch] and every wavefront then reduces some rows of it: of the row's 256
+// logits it emits the `cap` largest as (id, logit) pairs in a FIXED order (lane, then column),
+// their number, and the cut = the smallest emitted logit (as a key): every logit of the tile row
+// that was not emitted lies strictly below it.  The row kernel selects the K-th largest among the
+// emitted logits of all tiles and accepts it only if it is not below any tile's cut (then no
+// logit that was not emitted can reach it): exact, and certified per row.
+//   The emitted set is found by bisection, not on the logits themselves but on a monotone
+// 12-bit fixed-point image of them, q = trunc(1 + (z - min) * 4095 / (max - min)) (equal q:
+// both emitted or neither).  Then the halving runs on the scalar unit (integer bounds in
+// SGPRs); the vector unit only compares, one instruction per logit and halving, and wave
+// ballots + population counts do the counting.  13 steps end exactly at the smallest q whose
+// upper set holds at most `cap` logits.  If more than `cap` logits share the top q (massive
+// ties, or a non-finite logit, which collapses the image) the tile reports an overflowing count
+// and the row kernel reads the row whole.
+constexpr int kTileCols = 256;
+constexpr int kTilePitch = kTileCols + 8;   // floats; rows 4 apart fall into disjoint banks
+constexpr int kTileQBits = 12;
+
+// Rows q0 .. q0 + 3 of the tile; wrow[i] = window row index (b * L + s) of tile row q0 + i, or -1
+// if it is not a live window row; v0 = id of the tile's first column; tile / T = its index and the
+// number of tiles per row.  Uniform over the wavefront.
+__device__ __forceinline__ void tile_candidates4(const LmHeadArgs& a, const float* zt, int lane, int q0,
+                                                 const int (&wrow)[4], int v0, int tile, int T) {
+  const int cap = a.cand_cap;
+  const int nvalid = min(kTileCols, a.n - v0);           // columns of this tile that exist
+  constexpr uint32_t QMAX = (1u << kTileQBits) - 1u;
+  const bool ragged = nvalid < kTileCols;                // only the last tile of a row
+  bool ok[4];
+#pragma unroll
+  for (int e = 0; e < 4; ++e) ok[e] = 4 * lane + e < nvalid;
+  float v[4][4];
+  uint32_t q[4][4];                                      // 0 .. QMAX + 2; 0 also for a column that does not exist
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const float4 t = *reinterpret_cast<const float4*>(&zt[(q0 + i) * kTilePitch + 4 * lane]);
+    v[i][0] = t.x; v[i][1] = t.y; v[i][2] = t.z; v[i][3] = t.w;
+  }
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    float mx, mn;
+    if (!ragged) {
+      mx = fmaxf(fmaxf(v[i][0], v[i][1]), fmaxf(v[i][2], v[i][3]));
+      mn = fminf(fminf(v[i][0], v[i][1]), fminf(v[i][2], v[i][3]));
+    } else {
+      mx = -INFINITY;
+      mn = INFINITY;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        v[i][e] = ok[e] ? v[i][e] : 0.f;
+        mx = ok[e] ? fmaxf(mx, v[i][e]) : mx;
+        mn = ok[e] ? fminf(mn, v[i][e]) : mn;
+      }
+    }
+    // a NaN (or +inf next to -inf) among the four poisons their sum
+    const float sum4 = (v[i][0] + v[i][1]) + (v[i][2] + v[i][3]);
+    if (sum4 != sum4 && a.flags && wrow[i] >= 0) atomicOr(a.flags, 1);
+    const float hi = wave_max_f32(mx), lo = wave_min_f32(mn);
+    // q = trunc(1 + (z - lo) * scale), one fused multiply-add per logit: monotone in z.  For
+    // non-finite logits scale / shift degenerate, every q collapses and the tile row reports an
+    // overflow below.
+    const float scale = hi > lo ? __fdiv_rn(static_cast<float>(QMAX), hi - lo) : 0.f;
+    const float shift = 1.0f - lo * scale;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      q[i][e] = static_cast<uint32_t>(fmaxf(__fmaf_rn(v[i][e], scale, shift), 0.f));
+      if (ragged) q[i][e] = ok[e] ? q[i][e] : 0u;
+    }
+  }
+  // The largest c with #(q >= c) > cap, built bit by bit from the top (q < 2^(kTileQBits + 1)); the
+  // cut is c + 1.  One scalar unit serves the whole compute unit, so the loop is kept to ten scalar
+  // operations per row and step.  #(q >= 0) is the whole tile row: above cap unless the row has at
+  // most cap columns, which is handled apart.
+  uint32_t cq[4] = {0u, 0u, 0u, 0u};
+#pragma unroll 1
+  for (uint32_t bit = 1u << kTileQBits; bit != 0u; bit >>= 1) {
+    // the four rows side by side: all compares first, so that the scalar unit's population
+    // counts do not each wait for a compare of their own
+    unsigned long long m[4][4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+      for (int e = 0; e < 4; ++e) m[i][e] = __builtin_amdgcn_ballot_w64(q[i][e] >= cq[i] + bit);
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int n = __builtin_popcountll(m[i][0]) + __builtin_popcountll(m[i][1]) +
+                    __builtin_popcountll(m[i][2]) + __builtin_popcountll(m[i][3]);
+      cq[i] = n > cap ? cq[i] + bit : cq[i];
+    }
+  }
+  const unsigned long long below = (1ull << lane) - 1ull;        // lanes before this one
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    if (wrow[i] < 0) continue;                           // uniform
+    const bool all = nvalid <= cap;                      // the whole tile row is emitted: cut 0
+    const uint32_t cutq = all ? 0u : cq[i] + 1u;
+    // emitted logits in the fixed order (column within the lane, then lane)
+    bool take[4];
+    unsigned long long tm[4];
+    float vmin = INFINITY;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      take[e] = q[i][e] >= cutq && (!ragged || ok[e]);
+      tm[e] = __builtin_amdgcn_ballot_w64(take[e]);
+      vmin = take[e] ? fminf(vmin, v[i][e]) : vmin;
+    }
+    const int c0 = __builtin_popcountll(tm[0]), c1 = __builtin_popcountll(tm[1]),
+              c2 = __builtin_popcountll(tm[2]), c3 = __builtin_popcountll(tm[3]);
+    const int total = c0 + c1 + c2 + c3;
+    const int base[4] = {0, c0, c0 + c1, c0 + c1 + c2};
+    vmin = wave_min_f32(vmin);                           // smallest emitted logit (NaNs are never smallest)
+    const size_t slot = static_cast<size_t>(wrow[i]) * T + tile;
+    const bool fits = total > 0 && total <= cap;         // nothing emitted: more than cap tie at the top
+    if (fits) {
+      uint2* dst = a.cand + (static_cast<size_t>(wrow[i]) * kRowListCap + static_cast<size_t>(tile) * cap);
+#pragma unroll
+      for (int e = 0; e < 4; ++e)
+        if (take[e])
+          dst[base[e] + __builtin_popcountll(tm[e] & below)] =
+              make_uint2(static_cast<uint32_t>(v0 + 4 * lane + e), __float_as_uint(v[i][e]));
+    }
+    if (lane == 0) {
+      a.cand_cnt[slot] = fits ? static_cast<uint32_t>(total) : static_cast<uint32_t>(cap) + 1u;   // > cap: overflow
+      a.cand_cut[slot] = all ? 0u : zkey(vmin);
+    }
   }
 }
 
@@ -180,6 +331,9 @@ __global__ __launch_bounds__((Cfg<RBW, C, NWV>::THREADS)) void lm_head_kernel(
   const int mt = (id / 8) % MT;
   if (mapped_row(rm, xcd, jt, Cfg<RBW, C, NWV>::BN, 0) >= a.n) return;   // no row left for this tile
   const int rb0 = mt * RBW;
+  RowBlockDst rbd[RBW];
+#pragma unroll
+  for (int rbw = 0; rbw < RBW; ++rbw) rbd[rbw] = row_block_dst(a, min(rb0 + rbw, nRB - 1), nLb);
 
   const int tid = threadIdx.x;
   const int wave = tid >> 6;
@@ -353,7 +507,27 @@ __global__ __launch_bounds__((Cfg<RBW, C, NWV>::THREADS)) void lm_head_kernel(
   for (int t0 = 0; t0 < ntiles_pad - D; t0 += D) body(t0, TrueT{});
   body(ntiles_pad - D, FalseT{});
 
-  epilogue<RBW, C>(a, acc, nLb, nRB, rb0, mapped_row(rm, xcd, jt, K::BN, wave * 32 + ln), lg);
+  float zv[RBW][16];
+  epilogue<RBW, C>(a, acc, nRB, rb0, rbd, mapped_row(rm, xcd, jt, K::BN, wave * 32 + ln), lg, zv);
+
+  if constexpr (RBW == 1 && NWV == 8) {
+    // ---- per-tile candidates for the row kernel (a.cand is uniform) --------------------------
+    static_assert(K::BN == kTileCols && K::LDS_BYTES >= 32 * kTilePitch * 4, "logit tile must fit");
+    if (a.cand == nullptr) return;
+    __syncthreads();                       // every wavefront is done with the staging buffers
+    float* const zt = reinterpret_cast<float*>(lds_raw);
+#pragma unroll
+    for (int j = 0; j < 16; ++j) zt[((j >> 2) * 8 + lg * 4 + (j & 3)) * kTilePitch + wave * 32 + ln] = zv[0][j];
+    __syncthreads();
+    const RowBlockDst& r = rbd[0];
+    int wrow[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int s = r.sbase + wave * 4 + i;
+      wrow[i] = (rb0 < nRB && s < r.live) ? r.b * a.L + s : -1;
+    }
+    tile_candidates4(a, zt, lane, wave * 4, wrow, vt * K::BN, vt, VT);
+  }
 }
 
 // Scheduling pattern "one MFMA, then its share of OPS memory-side operations (LDS reads, LDS
@@ -407,6 +581,12 @@ __global__ __launch_bounds__(512) void lm_head_gemm8_kernel(const LmHeadArgs a, 
   if (vt >= VT) return;
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int wc = wave & 3, wr = wave >> 2;
+  // where this wavefront's two row blocks go, and the row block whose candidates it selects:
+  // fetched now, so that the epilogue does not begin with a round trip for the window starts
+  RowBlockDst rbd[2];
+#pragma unroll
+  for (int r2 = 0; r2 < 2; ++r2) rbd[r2] = row_block_dst(a, min(wr * 2 + r2, nRB - 1), nLb);
+  const RowBlockDst rbd_sel = row_block_dst(a, min(wave >> 1, nRB - 1), nLb);
   const int ln = lane & 31, lg = lane >> 5;
   const int chunk = tid & 7, trow = tid >> 3;          // row 0..63 of a 64-row pass
   const int d = a.d;
@@ -505,6 +685,13 @@ __global__ __launch_bounds__(512) void lm_head_gemm8_kernel(const LmHeadArgs a, 
     }
   }
 
+  float zv[2][2][16];                       // processed logits [column half][row block][element]
+#pragma unroll
+  for (int c = 0; c < 2; ++c)
+#pragma unroll
+    for (int r2 = 0; r2 < 2; ++r2)
+#pragma unroll
+      for (int j = 0; j < 16; ++j) zv[c][r2][j] = processed_logit<C>(a, acc[c][r2 * C][j], acc[c][r2 * C + C - 1][j]);
 #pragma unroll
   for (int c = 0; c < 2; ++c) {
     const int v = vt * K::BN + wc * 64 + c * 32 + ln;
@@ -513,11 +700,40 @@ __global__ __launch_bounds__(512) void lm_head_gemm8_kernel(const LmHeadArgs a, 
     for (int r2 = 0; r2 < 2; ++r2) {
       const int rb = wr * 2 + r2;
       if (rb >= nRB) break;
-      const RowBlockDst r = row_block_dst(a, rb, nLb);
+      const RowBlockDst& r = rbd[r2];
 #pragma unroll
-      for (int j = 0; j < 16; ++j)
-        store_logit<C>(a, r, r.sbase + (j >> 2) * 8 + lg * 4 + (j & 3), v, acc[c][r2 * C][j],
-                       acc[c][r2 * C + C - 1][j]);
+      for (int j = 0; j < 16; ++j) store_z(a, r, r.sbase + (j >> 2) * 8 + lg * 4 + (j & 3), v, zv[c][r2][j]);
+    }
+  }
+
+  if constexpr (K::LDS_BYTES >= 128 * kTilePitch * 4) {
+    // ---- per-tile candidates for the row kernel (a.cand is uniform) --------------------------
+    static_assert(K::BN == kTileCols, "logit tile width");
+    if (a.cand == nullptr) return;
+    __syncthreads();                       // (also the loop's last barrier) staging buffers are free
+    float* const zt = reinterpret_cast<float*>(lds_raw);
+#pragma unroll
+    for (int c = 0; c < 2; ++c)
+#pragma unroll
+      for (int r2 = 0; r2 < 2; ++r2)
+#pragma unroll
+        for (int j = 0; j < 16; ++j)
+          zt[((wr * 2 + r2) * 32 + (j >> 2) * 8 + lg * 4 + (j & 3)) * kTilePitch + wc * 64 + c * 32 + ln] = zv[c][r2][j];
+    __syncthreads();
+#pragma unroll 1
+    for (int g = 0; g < 4; ++g) {          // 16 tile rows per wavefront, four at a time
+      const int q0 = wave * 16 + g * 4;
+      const int rb = q0 >> 5;                // == wave >> 1
+      int wrow[4] = {-1, -1, -1, -1};
+      if (rb < nRB) {
+        const RowBlockDst& r = rbd_sel;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const int s = r.sbase + (q0 & 31) + i;
+          wrow[i] = s < r.live ? r.b * a.L + s : -1;
+        }
+      }
+      tile_candidates4(a, zt, lane, q0, wrow, vt * K::BN, vt, VT);
     }
   }
 }
@@ -553,6 +769,9 @@ __global__ __launch_bounds__((SplitCfg<RBW, C, KS>::THREADS)) void lm_head_split
   const int mt = (id / 8) % MT;
   if (mapped_row(rm, xcd, jt, 32, 0) >= n_) return;   // no row left for this tile
   const int rb0 = mt * RBW;
+  RowBlockDst rbd[RBW];                               // fetched now: not a round trip in the epilogue
+#pragma unroll
+  for (int rbw = 0; rbw < RBW; ++rbw) rbd[rbw] = row_block_dst(a, min(rb0 + rbw, nRB - 1), nLb);
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int ln = lane & 31, lg = lane >> 5, chunk = lane & 7, lrow = lane >> 3;
   const int d = d_;
@@ -674,7 +893,7 @@ __global__ __launch_bounds__((SplitCfg<RBW, C, KS>::THREADS)) void lm_head_split
   for (int rbw = 0; rbw < RBW; ++rbw) {
     const int rb = rb0 + rbw;
     if (rb >= nRB) break;
-    const RowBlockDst r = row_block_dst(a, rb, nLb);
+    const RowBlockDst& r = rbd[rbw];
 #pragma unroll
     for (int jj = 0; jj < 16 / NWAVE; ++jj) {
       const int j = wave + jj * NWAVE;
@@ -814,6 +1033,15 @@ hipError_t launch_c(const LmHeadArgs& a, hipStream_t s, const LaunchEvents& ev) 
 hipError_t launch_lm_head(const LmHeadArgs& a, hipStream_t s, hipEvent_t ev_start, hipEvent_t ev_stop) {
   const LaunchEvents ev{ev_start, ev_stop};
   return a.C == 2 ? launch_c<2>(a, s, ev) : launch_c<1>(a, s, ev);
+}
+
+int lm_head_tiles(const LmHeadArgs& a) {
+  const Variant v = choose(a);
+  const int tiles = (a.n + kTileCols - 1) / kTileCols;
+  if (tiles > kRowMaxTiles) return 0;
+  if (v.gemm8) return Gemm8Cfg<2>::LDS_BYTES >= 128 * kTilePitch * 4 && a.C == 2 ? tiles : 0;
+  if (!v.split && v.rbw == 1 && v.nw == 8) return tiles;
+  return 0;
 }
 
 int lm_head_kernel_name(const LmHeadArgs& a, char* buf, size_t cap) {

@@ -47,7 +47,7 @@ namespace {
 constexpr int THREADS = SCD_ROW_THREADS;
 constexpr int NW = THREADS / kWave;
 constexpr int NBINS = 4096;
-constexpr int kListCap = 6144;               // candidate ids per row (LDS list / slice output)
+constexpr int kListCap = kRowListCap;         // candidate ids per row (LDS list / slice or tile output)
 constexpr int PER_LIST = kListCap / THREADS; // candidates per thread
 constexpr int kDirectMaxN = 16384;           // whole row in registers up to this many ids
 constexpr int PER_DIRECT = kDirectMaxN / THREADS;   // (rows of half that size take half of them)
@@ -77,9 +77,6 @@ struct Small {
   int hamm[6];                   // (differing, compared) drafts 1, 2, 3 iterations apart
   int xnew[256];                 // the sequence's new drafts by ring slot
 };
-
-// key with -0 folded onto +0, so that key order == float order for non-NaNs
-__device__ __forceinline__ uint32_t zkey(float f) { return float_to_key(f == 0.f ? 0.f : f); }
 
 // hist[0..NBINS): find the bin holding the `need`-th largest element counting
 // from the top bin; lowers `need` by the population of the bins above it.
@@ -474,8 +471,8 @@ __global__ __launch_bounds__(ST) void slice_kernel(const int32_t* const pos_, co
   const int slice_len = (((n + P - 1) / P) + 3) & ~3;
   const int lo_id = p * slice_len;
   const int hi_id = min(n, lo_id + slice_len);
-  uint32_t* const cnt_out = a.cand_cnt + static_cast<size_t>(r) * 8;
-  uint32_t* const cut_out = a.cand_cut + static_cast<size_t>(r) * 8;
+  uint32_t* const cnt_out = a.cand_cnt + static_cast<size_t>(r) * P;
+  uint32_t* const cut_out = a.cand_cut + static_cast<size_t>(r) * P;
   if (lo_id >= hi_id) {
     if (tid == 0) {
       cnt_out[p] = 0;
@@ -1291,27 +1288,50 @@ __global__ __launch_bounds__(THREADS) void row_kernel(const int32_t* const pos_,
   } else if (filter && a.cand && P > 0) {
     // ---- candidates emitted by the slice kernel ----------------------------------
     uint32_t* hist = reinterpret_cast<uint32_t*>(smem + static_cast<size_t>((n + 7) & ~7) * 2);
-    // The 8 slice counts and cuts of the row (two 16-byte loads each) and the candidate
-    // slots themselves are fetched in ONE round trip: slots are read whether filled or not
-    // (always inside the row's kListCap pairs) and masked by the counts afterwards.
-    const uint4* cnt4 = reinterpret_cast<const uint4*>(a.cand_cnt + static_cast<size_t>(r) * 8);
-    const uint4* cut4 = reinterpret_cast<const uint4*>(a.cand_cut + static_cast<size_t>(r) * 8);
-    const uint4 cA = cnt4[0], cB = cnt4[1], qA = cut4[0], qB = cut4[1];
+    // The P counts and cuts of the row's lists (P slices of the slice kernel, or P column tiles
+    // of the LM head's epilogue; thread t holds those of list t), the count that governs each
+    // of this thread's candidate slots, and the slots themselves are fetched in ONE round trip:
+    // slots are read whether filled or not (always inside the row's kListCap pairs) and masked
+    // by the counts afterwards.
+    const uint32_t* const cntp = a.cand_cnt + static_cast<size_t>(r) * P;
+    const uint32_t* const cutp = a.cand_cut + static_cast<size_t>(r) * P;
+    uint32_t tc = 0, tq = 0;
+    if (tid < P) {
+      tc = cntp[tid];
+      tq = cutp[tid];
+    }
     const uint2* src = a.cand + static_cast<size_t>(r) * kListCap;
     uint2 raw[PER_LIST];
+    uint32_t slot_cnt[PER_LIST];
+    int slot_off[PER_LIST];
 #pragma unroll
-    for (int e = 0; e < PER_LIST; ++e) raw[e] = src[tid + e * THREADS];
-    const uint32_t cnt8[8] = {cA.x, cA.y, cA.z, cA.w, cB.x, cB.y, cB.z, cB.w};
-    const uint32_t cut8[8] = {qA.x, qA.y, qA.z, qA.w, qB.x, qB.y, qB.z, qB.w};
+    for (int e = 0; e < PER_LIST; ++e) {
+      const int i = tid + e * THREADS;
+      const int p = i / capE;
+      slot_off[e] = i - p * capE;
+      raw[e] = src[i];
+      slot_cnt[e] = cntp[p < P ? p : 0];
+      if (p >= P) slot_cnt[e] = 0;
+    }
+    // every list fits its capacity, how many candidates there are, the largest cut
+    {
+      const int tot = wave_sum_i32(static_cast<int>(tc <= static_cast<uint32_t>(capE) ? tc : 0u));
+      const uint32_t cm = wave_max_u32(tq);
+      const bool anybad = __ballot(tc > static_cast<uint32_t>(capE)) != 0ull;
+      if (lane == 0) {
+        sm.ired2[wave] = tot;
+        sm.wtot[wave] = cm;
+        sm.ired[wave] = anybad ? 1 : 0;
+      }
+    }
+    __syncthreads();                // their next writers sit behind the barrier of block_minmax
     bool fits = true;
     uint32_t cut_max = 0, total = 0;
 #pragma unroll
-    for (int p = 0; p < 8; ++p) {
-      if (p < P) {
-        fits &= cnt8[p] <= static_cast<uint32_t>(capE);
-        total += cnt8[p];
-        cut_max = cut8[p] > cut_max ? cut8[p] : cut_max;
-      }
+    for (int w = 0; w < NW; ++w) {
+      fits &= sm.ired[w] == 0;
+      total += static_cast<uint32_t>(sm.ired2[w]);
+      cut_max = sm.wtot[w] > cut_max ? sm.wtot[w] : cut_max;
     }
     if (fits && total >= static_cast<uint32_t>(a.top_k)) {
       int vid[PER_LIST];
@@ -1319,12 +1339,7 @@ __global__ __launch_bounds__(THREADS) void row_kernel(const int32_t* const pos_,
       bool ok[PER_LIST];
 #pragma unroll
       for (int e = 0; e < PER_LIST; ++e) {
-        const int i = tid + e * THREADS;
-        const int p = i / capE, o = i - p * capE;
-        uint32_t c = 0;
-#pragma unroll
-        for (int pp = 0; pp < 8; ++pp) c = (pp == p && pp < P) ? cnt8[pp] : c;
-        ok[e] = static_cast<uint32_t>(o) < c && raw[e].x < static_cast<uint32_t>(n);
+        ok[e] = static_cast<uint32_t>(slot_off[e]) < slot_cnt[e] && raw[e].x < static_cast<uint32_t>(n);
         vid[e] = ok[e] ? static_cast<int>(raw[e].x) : 0;
         zv[e] = ok[e] ? __uint_as_float(raw[e].y) : 0.f;
       }
@@ -1503,13 +1518,23 @@ size_t lds_bytes_for(int n) {
   return static_cast<size_t>((n + 7) & ~7) * 2 + NBINS * sizeof(uint32_t) + kListCap * sizeof(uint16_t);
 }
 
-inline size_t small_block(int rows) { return (static_cast<size_t>(rows) * 8 * 4 + 255) / 256 * 256; }
+inline size_t small_block(int rows) {
+  return (static_cast<size_t>(rows) * kRowMaxTiles * 4 + 255) / 256 * 256;
+}
 
 }  // namespace
 
 size_t row_candidate_bytes(int rows) {
-  // per row: kListCap (id, logit) pairs, 8 slice counts, 8 slice cuts
+  // per row: kListCap (id, logit) pairs, kRowMaxTiles list counts, kRowMaxTiles list cuts
   return static_cast<size_t>(rows) * kListCap * sizeof(uint2) + 2 * small_block(rows);
+}
+
+void row_candidate_layout(void* base_, int rows, uint2** cand, uint32_t** cnt, uint32_t** cut) {
+  char* base = static_cast<char*>(base_);
+  const size_t pairs = static_cast<size_t>(rows) * kListCap * sizeof(uint2);
+  *cand = reinterpret_cast<uint2*>(base);
+  *cnt = reinterpret_cast<uint32_t*>(base + pairs);
+  *cut = reinterpret_cast<uint32_t*>(base + pairs + small_block(rows));
 }
 
 bool row_uses_candidates(int n, int top_k) {
@@ -1523,23 +1548,25 @@ hipError_t launch_row(const RowArgs& a_in, hipStream_t s, size_t* lds_configured
   int P = 0, capE = 0;
   a.cand = nullptr;
   if (a.cand_base && row_uses_candidates(a.n, a.top_k)) {
-    P = (a.n + kSliceMax - 1) / kSliceMax;                     // <= 8 for n <= 65536
-    capE = kListCap / P;
-    int rank = (2 * a.top_k + P - 1) / P;
-    rank = rank < 64 ? 64 : rank;
-    if (rank > capE * 4 / 5) rank = capE * 4 / 5;
-    char* base = static_cast<char*>(a.cand_base);
-    const size_t pairs = static_cast<size_t>(a.rows) * kListCap * sizeof(uint2);
-    a.cand = reinterpret_cast<uint2*>(base);
-    a.cand_cnt = reinterpret_cast<uint32_t*>(base + pairs);
-    a.cand_cut = reinterpret_cast<uint32_t*>(base + pairs + small_block(a.rows));
-    if (a.rows * P > 512)
-      hipLaunchKernelGGL(slice_kernel<512>, dim3(a.rows * P), dim3(512), 0, s, a.pos, a.iter, a.mode, a.L, a.N, P,
-                         capE, rank, a);
-    else
-      hipLaunchKernelGGL(slice_kernel<THREADS>, dim3(a.rows * P), dim3(THREADS), 0, s, a.pos, a.iter, a.mode, a.L,
-                         a.N, P, capE, rank, a);
-    if (hipError_t e = hipGetLastError(); e != hipSuccess) return e;
+    row_candidate_layout(a.cand_base, a.rows, &a.cand, &a.cand_cnt, &a.cand_cut);
+    if (a.tiles > 0) {
+      // the LM head's epilogue has filled the lists: one per 256-column tile
+      P = a.tiles;
+      capE = kListCap / P;
+    } else {
+      P = (a.n + kSliceMax - 1) / kSliceMax;                     // <= 8 for n <= 65536
+      capE = kListCap / P;
+      int rank = (2 * a.top_k + P - 1) / P;
+      rank = rank < 64 ? 64 : rank;
+      if (rank > capE * 4 / 5) rank = capE * 4 / 5;
+      if (a.rows * P > 512)
+        hipLaunchKernelGGL(slice_kernel<512>, dim3(a.rows * P), dim3(512), 0, s, a.pos, a.iter, a.mode, a.L, a.N, P,
+                           capE, rank, a);
+      else
+        hipLaunchKernelGGL(slice_kernel<THREADS>, dim3(a.rows * P), dim3(THREADS), 0, s, a.pos, a.iter, a.mode, a.L,
+                           a.N, P, capE, rank, a);
+      if (hipError_t e = hipGetLastError(); e != hipSuccess) return e;
+    }
   }
   const size_t lds = lds_bytes_for(a.n);
   // The dynamic-LDS limit is an attribute of the function on a device.  Every context asks

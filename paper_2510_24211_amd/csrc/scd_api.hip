@@ -29,6 +29,8 @@ bool valid_config(const scd_config* c) {
   if (c->N < 1 || c->V < 1) return false;
   if (c->d < 0 || (c->d % 8) != 0) return false;
   if (c->v_lo < 0 || c->v_hi <= c->v_lo || c->v_hi > c->V) return false;
+  // the kernels index the logits of one sequence's window with 32 bits
+  if (static_cast<int64_t>(c->L) * (c->v_hi - c->v_lo) >= (static_cast<int64_t>(1) << 31)) return false;
   if (c->top_k < 0) return false;
   if (!(c->temperature > 0.f) || !std::isfinite(c->temperature)) return false;
   if (!std::isfinite(c->cfg_lambda)) return false;
@@ -143,7 +145,7 @@ inline T* field(const scd_ctx* c, void* st, int f) {
 inline int hip_rc(hipError_t e) { return e == hipSuccess ? SCD_OK : SCD_EHIP; }
 inline bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
 
-int run_tail(scd_ctx* c, void* st) {
+int run_tail(scd_ctx* c, void* st, int tiles = 0) {
   // z of this iteration is in place in the ring.
   const size_t half = static_cast<size_t>(c->cfg.B) * c->cfg.L * c->n;
   if (c->n <= scd::kRowKernelMaxN) {
@@ -176,6 +178,7 @@ int run_tail(scd_ctx* c, void* st) {
     ra.top_p24 = top_p24_of(c->cfg);
     ra.v_lo = c->cfg.v_lo; ra.seed = c->cfg.seed;
     ra.cand_base = static_cast<char*>(c->ws) + small_need(c->cfg);
+    ra.tiles = tiles;            // > 0: the LM head has already written the candidate lists
     ra.gumbel = c->cfg.coupling == SCD_COUPLING_GS;
     ra.alpha = 1.0f - c->cfg.sjd_mix;
     ra.g = field<int32_t>(c, st, SCD_F_G);
@@ -457,11 +460,25 @@ int scd_step(scd_ctx* c, const uint16_t* d_h, const uint16_t* d_W, void* st) {
   a.lam = c->cfg.cfg_lambda;
   a.one_plus_lam = 1.0f + c->cfg.cfg_lambda;
   a.tau = c->cfg.temperature;
+  // First half of the top-k selection inside the LM head's epilogue (per-tile candidate lists in
+  // the workspace) when the kernel for this shape can do it and the lists are long enough: on
+  // average a tile holds top_k / tiles of the row's top_k logits; demand twice that plus 8.
+  int tiles = 0;
+  if (scd::row_uses_candidates(c->n, c->cfg.top_k)) {
+    const int t = scd::lm_head_tiles(a);
+    if (t > 0 && 2L * c->cfg.top_k <= static_cast<long>(t) * (scd::kRowListCap / t - 8)) tiles = t;
+  }
+  if (tiles > 0) {
+    scd::row_candidate_layout(static_cast<char*>(c->ws) + small_need(c->cfg), c->cfg.B * c->cfg.L, &a.cand,
+                              &a.cand_cnt, &a.cand_cut);
+    a.cand_cap = scd::kRowListCap / tiles;
+    a.flags = field<int32_t>(c, st, SCD_F_FLAGS);
+  }
   const bool timed = c->ev_start && c->ev_stop;
   if (hipError_t e = scd::launch_lm_head(a, c->stream, timed ? c->ev_start : nullptr, timed ? c->ev_stop : nullptr);
       e != hipSuccess)
     return SCD_EHIP;
-  return run_tail(c, st);
+  return run_tail(c, st, tiles);
 }
 
 int scd_set_lm_head_events(scd_ctx* c, void* ev_start, void* ev_stop) {

@@ -55,6 +55,8 @@ __device__ __forceinline__ uint32_t float_to_key(float f) {
 __device__ __forceinline__ float key_to_float(uint32_t k) {
   return __uint_as_float((k & 0x80000000u) ? (k & 0x7FFFFFFFu) : ~k);
 }
+// key with -0 folded onto +0, so that key order == float order for non-NaNs
+__device__ __forceinline__ uint32_t zkey(float f) { return float_to_key(f == 0.f ? 0.f : f); }
 
 // ---- wavefront collectives ---------------------------------------------------------
 // Lane exchanges through the vector ALU's data-parallel primitives (DPP) and v_readlane:
@@ -103,6 +105,21 @@ __device__ __forceinline__ uint32_t wave_max_u32(uint32_t v) {
                static_cast<uint32_t>(__builtin_amdgcn_readlane(i, 16))),
             mx(static_cast<uint32_t>(__builtin_amdgcn_readlane(i, 32)),
                static_cast<uint32_t>(__builtin_amdgcn_readlane(i, 48))));
+}
+// Largest / smallest value over the wavefront (NaNs are ignored unless every lane holds one).
+__device__ __forceinline__ float wave_max_f32(float v) {
+  v = fmaxf(v, dpp_f32<kDppXor1>(v));
+  v = fmaxf(v, dpp_f32<kDppXor2>(v));
+  v = fmaxf(v, dpp_f32<kDppHalfMirror>(v));
+  v = fmaxf(v, dpp_f32<kDppMirror>(v));
+  return fmaxf(fmaxf(readlane_f32(v, 0), readlane_f32(v, 16)), fmaxf(readlane_f32(v, 32), readlane_f32(v, 48)));
+}
+__device__ __forceinline__ float wave_min_f32(float v) {
+  v = fminf(v, dpp_f32<kDppXor1>(v));
+  v = fminf(v, dpp_f32<kDppXor2>(v));
+  v = fminf(v, dpp_f32<kDppHalfMirror>(v));
+  v = fminf(v, dpp_f32<kDppMirror>(v));
+  return fminf(fminf(readlane_f32(v, 0), readlane_f32(v, 16)), fminf(readlane_f32(v, 32), readlane_f32(v, 48)));
 }
 __device__ __forceinline__ int wave_sum_i32(int v) {
   v += dpp_i32<kDppXor1>(v);

@@ -17,6 +17,16 @@ struct LmHeadArgs {
   size_t parity_stride; // floats between the two halves of z
   int B, C, L, N, d, n;
   float lam, one_plus_lam, tau;
+  // Optional (scd_step only, and only when lm_head_tiles() says the chosen kernel can): the
+  // epilogue also emits, per window row and per 256-column tile, the tile's cand_cap largest
+  // logits as (id, logit) pairs, their number and the cut below which nothing was emitted --
+  // the input of the row kernel's candidate path, which then needs no slice kernel.  Layout as
+  // row_candidate_layout() gives it; window row index = b * L + s.  All null / 0 => off.
+  uint2* cand;
+  uint32_t* cand_cnt;
+  uint32_t* cand_cut;
+  int cand_cap;         // pairs per (row, tile)
+  int32_t* flags;       // numeric-fault bits (NaN logits are reported here), may be null
 };
 // ev_start / ev_stop (both or neither): events that take the kernel's own start and stop time
 hipError_t launch_lm_head(const LmHeadArgs& a, hipStream_t s, hipEvent_t ev_start = nullptr,
@@ -24,6 +34,9 @@ hipError_t launch_lm_head(const LmHeadArgs& a, hipStream_t s, hipEvent_t ev_star
 // Name (as a profiler prints it, without namespaces and arguments) of the kernel that
 // launch_lm_head picks for these sizes (only B, C, L, d, n are read); snprintf semantics.
 int lm_head_kernel_name(const LmHeadArgs& a, char* buf, size_t cap);
+// Number of 256-column tiles per row if the kernel that launch_lm_head picks for these sizes can
+// emit per-tile candidates, else 0 (only B, C, L, d, n are read).
+int lm_head_tiles(const LmHeadArgs& a);
 
 // ---- top-k threshold + softmax normaliser -------------------------------
 struct SelectArgs {
@@ -117,11 +130,19 @@ struct RowArgs {
   // scratch for the slice kernel (rows longer than 8192 ids): row_candidate_bytes(rows)
   // bytes of device memory, 256-byte aligned, or null (then rows are processed whole)
   void* cand_base;
+  // tiles > 0: the LM head's epilogue has already filled the candidate scratch with `tiles`
+  // lists of kRowListCap / tiles pairs per row (launch_row then skips the slice kernel)
+  int tiles;
   uint2* cand;           // set by launch_row
   uint32_t* cand_cnt;    // set by launch_row
   uint32_t* cand_cut;    // set by launch_row
 };
 size_t row_candidate_bytes(int rows);
+// Where the candidate scratch (row_candidate_bytes(rows) bytes at base) keeps its parts: per row
+// kRowListCap (id, logit) pairs, then kRowMaxTiles counts, then kRowMaxTiles cuts.
+constexpr int kRowListCap = 6144;
+constexpr int kRowMaxTiles = 256;
+void row_candidate_layout(void* base, int rows, uint2** cand, uint32_t** cnt, uint32_t** cut);
 // whether launch_row, given scratch, runs the slice kernel for rows of n ids under this top-k
 bool row_uses_candidates(int n, int top_k);
 // lds_configured: the caller's record (one per context, initially 0) that the dynamic-LDS limit of

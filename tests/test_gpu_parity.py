@@ -362,6 +362,41 @@ def test_lockstep_C2_fullV_full():
     assert ls.oracle.done() and st["steps"] == 415
 
 
+# ------------------- first half of the top-k selection inside the LM head's epilogue (wide vocabularies)
+@pytest.mark.parametrize("kw", [
+    dict(name="fvs", N=96, V=52000, d=128, top_k=2000, v_lo=0, v_hi=52000),              # 204 column tiles of 256
+    dict(name="fvr", N=70, L=20, V=60000, d=136, top_k=1500, v_lo=5, v_hi=51290),         # ragged ids, window, k
+    dict(name="fvg", N=200, L=64, B=2, V=52000, d=128, top_k=2000, v_lo=0, v_hi=52000),   # all rows in one workgroup
+    dict(name="fv3", N=60, L=20, B=3, V=51210, d=192, top_k=1800, v_lo=0, v_hi=51210),    # 3 row blocks, ragged tile
+])
+def test_lockstep_epilogue_candidates_scaled(kw):
+    _lockstep(wl.scaled(wl.WORKLOADS["C2"], **kw))
+
+
+def test_lockstep_epilogue_candidates_with_ties_that_overflow_a_tile():
+    # 40 identical weight rows inside one 256-column tile, with a large norm: in about half of the
+    # window rows their (identical) logits are the row's largest, more than a tile's list holds;
+    # those rows must fall back to reading the whole row.  300 more identical rows spread over the
+    # vocabulary tie at the top-k boundary region without overflowing any list.
+    import lockstep
+    w = wl.scaled(wl.WORKLOADS["C2"], name="fvt", N=64, V=52000, d=128, top_k=2000, v_lo=0, v_hi=52000, seed=77)
+    W = wl.lm_head_weight(w)
+    g = np.random.default_rng(5)
+    hot = wl.f32_to_bf16_bits((g.standard_normal(w.d) * 0.1).astype(np.float32))
+    W[1000:1040] = hot                                   # one tile (columns 768..1023 + 1024..1279: rows 1000-1023 / 1024-1039)
+    W[3100:3140] = hot                                   # inside one tile (3072..3327)
+    warm = wl.f32_to_bf16_bits((g.standard_normal(w.d) * 0.03).astype(np.float32))
+    W[np.arange(300) * 170 + 7] = warm
+    key = (w.seed, w.V, w.d, w.w_std, w.v_lo, w.v_hi, str(DEV))
+    lockstep._W_CACHE.clear()
+    lockstep._W_CACHE[key] = (_bf16(W), lg.bf16_bits_to_f64(W[w.v_lo:w.v_hi]))
+    try:
+        ls, st = _lockstep(w)
+    finally:
+        lockstep._W_CACHE.clear()
+    assert ls.oracle.done()
+
+
 # ----------------------------------------- Gumbel-sharing coupling (pi_GS)
 @pytest.mark.parametrize("kw", [
     dict(N=64, L=8, seed=0),                        # the toy workload itself
