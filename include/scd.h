@@ -42,6 +42,10 @@
  *   - "Allowed ids" A = [v_lo, v_hi), n = |A|.  Tokens in x / y / the state are
  *     OFFSETS into A (0..n-1); emitted tokens (out) are real ids v_lo + offset.
  *     Processed logits z hold only the n allowed columns.
+ *   - Rows of up to 65536 allowed ids run through one fused kernel per row (plus the LM
+ *     head).  Longer rows are supported with top-k and the maximal coupling only (one kernel
+ *     per stage: select, MRS, commit); Gumbel sharing, sjd_mix > 0, top_p and diagnostics on
+ *     such rows are refused by scd_create with SCD_EUNSUPPORTED.
  *   - Window order: row s of a [B, L, ...] array belongs to position pos0[b]+s.
  *     Lw_b = min(L, N - pos0[b]) rows are live; the rest are ignored on input
  *     and written as y = -1, k = 1 on output.

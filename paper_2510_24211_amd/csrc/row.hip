@@ -78,6 +78,25 @@ struct Small {
   int xnew[256];                 // the sequence's new drafts by ring slot
 };
 
+// Lexicographic (score, id) minimum over the per-wavefront entries in LDS.  All entries are read
+// first and folded with selects: a chain of compare-and-branch steps waits for one LDS round
+// trip per entry (about a microsecond for 16 wavefronts).
+__device__ __forceinline__ void block_min_score_id(const Small& sm, float& best, int& best_id) {
+  float ss[NW];
+  int si[NW];
+#pragma unroll
+  for (int w = 0; w < NW; ++w) {
+    ss[w] = sm.s_score[w];
+    si[w] = sm.s_id[w];
+  }
+#pragma unroll
+  for (int w = 0; w < NW; ++w) {
+    const bool better = (ss[w] < best) | ((ss[w] == best) & (si[w] < best_id));
+    best = better ? ss[w] : best;
+    best_id = better ? si[w] : best_id;
+  }
+}
+
 // hist[0..NBINS): find the bin holding the `need`-th largest element counting
 // from the top bin; lowers `need` by the population of the bins above it.
 // The trailing barrier keeps a later writer of sel_bin / sel_above / wtot away from slow
@@ -1307,7 +1326,7 @@ __global__ __launch_bounds__(THREADS) void row_kernel(const int32_t* const pos_,
 #pragma unroll
     for (int e = 0; e < PER_LIST; ++e) {
       const int i = tid + e * THREADS;
-      const int p = i / capE;
+      const int p = static_cast<int>(__umulhi(static_cast<uint32_t>(i), a.cand_recip));   // i / capE
       slot_off[e] = i - p * capE;
       raw[e] = src[i];
       slot_cnt[e] = cntp[p < P ? p : 0];
@@ -1367,13 +1386,7 @@ __global__ __launch_bounds__(THREADS) void row_kernel(const int32_t* const pos_,
       sm.s_id[wave] = best_id;
     }
     __syncthreads();
-#pragma unroll
-    for (int w = 0; w < NW; ++w) {
-      if (sm.s_score[w] < best || (sm.s_score[w] == best && sm.s_id[w] < best_id)) {
-        best = sm.s_score[w];
-        best_id = sm.s_id[w];
-      }
-    }
+    block_min_score_id(sm, best, best_id);
     if (best_id != 0x7FFFFFFF) {   // else: empty residual (rounding only) counts as accept
       y_out = best_id;
       k_out = 0;
@@ -1391,13 +1404,7 @@ __global__ __launch_bounds__(THREADS) void row_kernel(const int32_t* const pos_,
       sm.s_id[wave] = gi;
     }
     __syncthreads();
-#pragma unroll
-    for (int w = 0; w < NW; ++w) {
-      if (sm.s_score[w] < gb || (sm.s_score[w] == gb && sm.s_id[w] < gi)) {
-        gb = sm.s_score[w];
-        gi = sm.s_id[w];
-      }
-    }
+    block_min_score_id(sm, gb, gi);
     // empty support cannot happen (the maximum is kept); -1: the row made no such draw
     g_out = out.prace ? (gi != 0x7FFFFFFF ? gi : R.x) : -1;
   }
@@ -1590,6 +1597,7 @@ hipError_t launch_row(const RowArgs& a_in, hipStream_t s, size_t* lds_configured
   const bool topp = a.top_p24 != 0u || a.diag != nullptr;   // the instances with the optional parts
   auto* const kernel = gs ? (topp ? row_kernel<true, true> : row_kernel<true, false>)
                           : (topp ? row_kernel<false, true> : row_kernel<false, false>);
+  a.cand_recip = capE > 0 ? static_cast<uint32_t>(((1ull << 32) + capE - 1) / capE) : 0u;
   hipLaunchKernelGGL(kernel, dim3(a.rows), dim3(THREADS), lds, s, a.pos, a.iter, a.mode, a.L, a.N, P, capE, a);
   return hipGetLastError();
 }

@@ -133,6 +133,7 @@ struct RowArgs {
   // tiles > 0: the LM head's epilogue has already filled the candidate scratch with `tiles`
   // lists of kRowListCap / tiles pairs per row (launch_row then skips the slice kernel)
   int tiles;
+  uint32_t cand_recip;   // set by launch_row: ceil(2^32 / pairs per candidate list)
   uint2* cand;           // set by launch_row
   uint32_t* cand_cnt;    // set by launch_row
   uint32_t* cand_cut;    // set by launch_row

@@ -111,7 +111,10 @@ def _select_case(z, top_k, top_p=0.0):
 @pytest.mark.parametrize("n,top_k", [(1024, 0), (1024, 100), (1000, 1), (1000, 999), (1000, 1000),
                                      (1000, 5000), (8192, 2000), (65536, 2000), (16384, 1000),
                                      (64000, 2000), (5, 2), (1, 1), (4097, 33),
-                                     (40000, 3500), (65536, 10000), (20000, 19999), (30001, 7)])
+                                     (40000, 3500), (65536, 10000), (20000, 19999), (30001, 7),
+                                     # rows longer than the fused kernel takes: the per-stage kernels
+                                     (65537, 2000), (70000, 500), (131072, 2000), (100003, 0),
+                                     (131072, 131071)])
 def test_select_softmax_against_oracle(n, top_k):
     g = np.random.default_rng(n * 31 + top_k)
     z = (g.standard_normal((6, n)) * 3).astype(np.float32)
@@ -150,6 +153,10 @@ def test_select_nucleus_against_oracle(n, top_k, top_p):
     (3, 5, 37, 7, 50, [0, 45, 49], 0.0),       # tiny vocabulary, windows of 5 / 5 / 1 rows
     (2, 16, 4096, 500, 100, [0, 90], 0.7),     # nucleus filter after top-k
     (1, 24, 20000, 0, 64, [5], 0.9),           # nucleus filter alone on a long row (in-place path)
+    # rows longer than 65536 ids: select_kernel -> mrs_kernel -> commit_kernel
+    (2, 6, 70000, 500, 40, [0, 37], 0.0),      # second window clipped to 3 rows
+    (1, 5, 131072, 2000, 64, [9], 0.0),
+    (1, 4, 100003, 0, 64, [62], 0.0),          # no filter, ragged n, window clipped to 2 rows
 ])
 def test_couple_draft_and_verify_against_oracle(Bn, L, n, top_k, N, pos0, top_p):
     g = np.random.default_rng(n + L)
