@@ -169,13 +169,16 @@ def cpu_baseline(w, seconds, coupling="mc", sjd_mix=0.0):
             "kind": "oracle", "tokens_per_s": float(tokens) / T,
             "sample": f"{steps} iterations of {w.name} ({decodes} whole decodes and the start of the "
                       f"next; {positions} window positions, {tokens} tokens) in {T:.1f} s, NumPy fp64",
-            "flagged_draws": flagged}
+            # fragile decisions of this oracle-only sample, counted with the oracle's a-priori
+            # band (no second implementation's logits beside it): 1e-5 (1 + 2 lambda) max(1, |thr|)
+            # around the top-k threshold, 1e-5 on accept and residual draws
+            "flagged_draws": dict(flagged, band="a-priori")}
 
 
 COMPANIONS = ("C2", "C1", "C3", "C4")
 # what a companion object keeps of a workload's result
 COMPANION_KEYS = ("value", "unit", "tokens_per_s", "steps", "warmup", "repeats", "ms_per_step",
-                  "ms_per_step_min", "ms_per_step_max", "config", "roofline")
+                  "ms_per_step_min", "ms_per_step_max", "config", "roofline", "parity_flags")
 
 
 def main():
@@ -423,6 +426,11 @@ def measure(a, name, inputs):
                    "setup_s": t_setup},
         "roofline": roof,
     }
+    # flagged / adopted decisions of this workload's lock-step parity run against the CPU oracle
+    # (a tracked record of the GPU tests; the bench itself compares nothing)
+    fpath = os.path.join(ROOT, "profiles", "parity_flags.json")
+    plain = a.coupling == "mc" and a.sjd_mix == 0.0      # the record is of the default coupling
+    out["parity_flags"] = (json.load(open(fpath)).get(w.name) if plain and os.path.exists(fpath) else None)
     if a.diagnostics:       # means over the rows of the recorded decode (Sec. 3 of the paper)
         ds, hs_ = diag_sum.cpu().numpy(), hamm_sum.cpu().numpy()
         rows = max(ds[3], 1.0)
