@@ -342,12 +342,21 @@ def measure(a, name, inputs):
             s.set_lm_head_events(None, None)
         check_reproduced()
         work = per_step[idx].sum(axis=0)
-        return dict(T=T, verified=int(work[0]), tokens=int(work[1]), enqueue_us=t_enq / K * 1e6)
+        return dict(T=T, verified=int(work[0]), tokens=int(work[1]), enqueue_us=t_enq / K * 1e6,
+                    first_step=int(idx[0]))
 
+    # The passes are spread evenly over the decode (untimed steps between them): its first
+    # iterations, where every draft is a fresh uniform draw and nearly every row rejects, are a
+    # transient of a few percent of the decode and would otherwise be all that K << nfe steps see.
+    gap = max(0, (nfe - Wm - R * K) // R) if whole else 0
     s.reset(st)
     if Wm > 0:
         run_steps(Wm)
-    passes = [timed_pass() for _ in range(R)]
+    passes = []
+    for r in range(R):
+        passes.append(timed_pass())
+        if gap and r + 1 < R:
+            run_steps(gap)
     # A step whose LM head carries the events is about a microsecond slower (the dispatch then
     # reports its timestamps), so the throughput comes from the passes without them and the
     # LM-head timing from one more identical pass with them.
@@ -418,8 +427,11 @@ def measure(a, name, inputs):
                                f"(synthetic drift model)",
                    "decode_iterations": int(nfe) if whole else None,
                    "tokens_per_iteration": w.B * w.N / nfe if whole else None,
-                   "timed": f"{R} passes of {K} steps continuing one decode after {Wm} warm-up steps"
-                            + (" (a pass = one whole decode)" if whole and K == nfe and Wm == 0 else ""),
+                   "timed": f"{R} passes of {K} steps of one decode after {Wm} warm-up steps"
+                            + (" (a pass = one whole decode)" if whole and K == nfe and Wm == 0 else
+                               f", {gap} untimed steps between passes (evenly spread over the decode)" if gap
+                               else ", back to back"),
+                   "first_step_of_each_pass": [p["first_step"] for p in passes],
                    "ms_per_step_all_passes": [p["T"] / K * 1e3 for p in passes],
                    "ms_per_step_with_events": None if T_ev is None else T_ev / K * 1e3,
                    "host_enqueue_us_per_step": med["enqueue_us"],
