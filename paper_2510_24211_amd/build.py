@@ -7,7 +7,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libscd.so")
-SOURCES = ["scd_api.hip", "lm_head.hip", "row.hip", "select.hip", "mrs.hip", "commit.hip",
+SOURCES = ["scd_api.hip", "lm_head.hip", "row.hip", "row_batched.hip", "select.hip", "mrs.hip", "commit.hip",
            "workload_gather.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
          # the method's fp32 roundings are part of its definition: no fused contraction

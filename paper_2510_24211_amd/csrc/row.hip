@@ -24,8 +24,9 @@
 //                 cut (then no unseen logit can be >= it): exact, verified.
 //                 Sum of exponentials, accept test, residual race and the
 //                 commit follow from the same registers.
-// Rows of <= 8192 logits skip the slice kernel (the whole row fits the row
-// kernel's registers).  If the verification fails (massive ties, adversarial
+// Rows of <= 16384 logits need no candidates (the whole row fits the row
+// kernel's registers); on longer ones the lists come from the LM head's
+// epilogue, one per 256-column tile, when that kernel emits them.  If the verification fails (massive ties, adversarial
 // layouts) or top-k is off, the row kernel falls back to a complete in-place
 // path: one coalesced read of the row, 16-bit key prefixes parked in LDS,
 // histogram select, candidate list or in-place scans.
@@ -33,8 +34,25 @@
 // whose bins adapt to the key range, so lanes rarely collide); all
 // floating-point sums use a fixed assignment of ids to threads and a fixed
 // reduction tree, so results are run-to-run identical.
+//
+// This file is compiled twice.  The second time (row_batched.hip defines
+// SCD_ROW_BATCHED) with 512 threads per row and rows of at most 8192 ids: such a
+// workgroup takes 122 registers per lane and 64 KB of LDS, so two of them share a
+// CU, and when there are more rows than CUs the barrier-separated phases of one
+// row overlap with another's instead of the rows queueing in rounds.  With few
+// rows the 1024-thread form is faster (half the work per lane).
 #include "scd_device.h"
 #include "scd_kernels.h"
+
+#ifdef SCD_ROW_BATCHED
+#define SCD_ROW_THREADS 512
+#define SCD_ROW_DIRECT_MAX 8192
+#define row_kernel row_kernel_batched        // distinct names in traces
+#define slice_kernel slice_kernel_batched
+#define LAUNCH_ROW launch_row_batched
+#else
+#define LAUNCH_ROW launch_row
+#endif
 
 namespace scd {
 namespace {
@@ -49,7 +67,10 @@ constexpr int NW = THREADS / kWave;
 constexpr int NBINS = 4096;
 constexpr int kListCap = kRowListCap;         // candidate ids per row (LDS list / slice or tile output)
 constexpr int PER_LIST = kListCap / THREADS; // candidates per thread
-constexpr int kDirectMaxN = 16384;           // whole row in registers up to this many ids
+#ifndef SCD_ROW_DIRECT_MAX
+#define SCD_ROW_DIRECT_MAX 16384
+#endif
+constexpr int kDirectMaxN = SCD_ROW_DIRECT_MAX;   // whole row in registers up to this many ids
 constexpr int PER_DIRECT = kDirectMaxN / THREADS;   // (rows of half that size take half of them)
 constexpr int kSliceMax = 8192;              // logits per slice workgroup
 constexpr int PER_SLICE = kSliceMax / THREADS;
@@ -1531,6 +1552,7 @@ inline size_t small_block(int rows) {
 
 }  // namespace
 
+#ifndef SCD_ROW_BATCHED
 size_t row_candidate_bytes(int rows) {
   // per row: kListCap (id, logit) pairs, kRowMaxTiles list counts, kRowMaxTiles list cuts
   return static_cast<size_t>(rows) * kListCap * sizeof(uint2) + 2 * small_block(rows);
@@ -1549,8 +1571,18 @@ bool row_uses_candidates(int n, int top_k) {
   return n > kDirectMaxN && n <= kRowKernelMaxN && filter && top_k <= kListCap / 2;
 }
 
-hipError_t launch_row(const RowArgs& a_in, hipStream_t s, size_t* lds_configured) {
+#endif  // !SCD_ROW_BATCHED
+
+hipError_t LAUNCH_ROW(const RowArgs& a_in, hipStream_t s, size_t* lds_configured) {
   if (a_in.rows <= 0) return hipSuccess;
+#ifdef SCD_ROW_BATCHED
+  if (a_in.n > kDirectMaxN) return hipErrorInvalidValue;     // this build holds whole rows in registers only
+#else
+  // more rows than compute units (256 on this chip), short rows, the hot instances: the build
+  // of this file whose workgroups pair up on a CU
+  if (a_in.rows > 256 && a_in.n <= kRowBatchedMaxN && a_in.top_p24 == 0u && a_in.diag == nullptr)
+    return launch_row_batched(a_in, s, lds_configured ? lds_configured + 1 : nullptr);
+#endif
   RowArgs a = a_in;
   int P = 0, capE = 0;
   a.cand = nullptr;

@@ -133,7 +133,7 @@ struct scd_ctx {
   int n;   // allowed ids
   int C;   // LM-head rows per window position
   hipEvent_t ev_start, ev_stop;   // optional instrumentation around the LM-head kernel
-  size_t row_lds;                 // dynamic-LDS limit already set for the row kernels (launch_row)
+  size_t row_lds[2];              // dynamic-LDS limit already set for the row kernels (launch_row, both builds)
 };
 
 namespace {
@@ -189,7 +189,7 @@ int run_tail(scd_ctx* c, void* st, int tiles = 0) {
       ra.xhist = field<int32_t>(c, st, SCD_F_XHIST);
       ra.phist = field<int32_t>(c, st, SCD_F_PHIST);
     }
-    return hip_rc(scd::launch_row(ra, c->stream, &c->row_lds));
+    return hip_rc(scd::launch_row(ra, c->stream, c->row_lds));
   }
   // rows too long for the LDS-resident kernel: select -> MRS -> commit
   scd::SelectArgs sa{};
@@ -273,7 +273,7 @@ int scd_create(scd_ctx** out, const scd_config* cfg, void* d_workspace, size_t w
   c->C = cfg->cfg_lambda != 0.f ? 2 : 1;
   c->ev_start = nullptr;
   c->ev_stop = nullptr;
-  c->row_lds = 0;
+  c->row_lds[0] = c->row_lds[1] = 0;
   // Set-up for scd_couple_draft_static: look the scratch address of the current device up now,
   // outside any stream capture.  Best effort (a host without a GPU can still create a context to
   // query layouts); the entry point repeats the lookup if it is still missing.
@@ -347,7 +347,7 @@ int select_impl(scd_ctx* c, char* ws, const float* d_z, int32_t rows, float* d_t
     ra.B = c->cfg.B; ra.L = c->cfg.L; ra.N = c->cfg.N; ra.n = c->n; ra.top_k = c->cfg.top_k;
     ra.top_p24 = top_p24_of(c->cfg);
     if (rows <= c->cfg.B * c->cfg.L) ra.cand_base = ws + small_need(c->cfg);
-    return hip_rc(scd::launch_row(ra, c->stream, &c->row_lds));
+    return hip_rc(scd::launch_row(ra, c->stream, c->row_lds));
   }
   scd::SelectArgs a{};
   a.z = d_z; a.thr = d_thr; a.lse = d_lse; a.nkept = d_nkept;
@@ -385,7 +385,7 @@ int couple_draft_impl(scd_ctx* c, char* w, const float* d_z_cur, const float* d_
     ra.top_p24 = top_p24_of(c->cfg);
     ra.v_lo = c->cfg.v_lo; ra.seed = c->cfg.seed;
     ra.cand_base = w + small_need(c->cfg);
-    return hip_rc(scd::launch_row(ra, c->stream, &c->row_lds));
+    return hip_rc(scd::launch_row(ra, c->stream, c->row_lds));
   }
   if (int rc = select_impl(c, w, d_z_cur, rows, thr_c, lse_c, nk_c); rc != SCD_OK) return rc;
   scd::MrsArgs a{};

@@ -146,9 +146,14 @@ constexpr int kRowMaxTiles = 256;
 void row_candidate_layout(void* base, int rows, uint2** cand, uint32_t** cnt, uint32_t** cut);
 // whether launch_row, given scratch, runs the slice kernel for rows of n ids under this top-k
 bool row_uses_candidates(int n, int top_k);
-// lds_configured: the caller's record (one per context, initially 0) that the dynamic-LDS limit of
-// the row kernels has been set on its device; null => set it on every launch
+// lds_configured: the caller's record (two words per context, initially 0) that the dynamic-LDS
+// limit of the row kernels has been set on its device; null => set it on every launch
 hipError_t launch_row(const RowArgs& a, hipStream_t s, size_t* lds_configured);
+// The same kernels built with 512 threads per row for rows of at most kRowBatchedMaxN ids (two
+// workgroups per compute unit); launch_row hands over to it when there are more rows than
+// compute units.  lds_configured: one word.
+constexpr int kRowBatchedMaxN = 8192;
+hipError_t launch_row_batched(const RowArgs& a, hipStream_t s, size_t* lds_configured);
 
 // ---- first rejection, emit, slide -----------------------------------------
 struct CommitArgs {

@@ -126,6 +126,21 @@ def test_select_softmax_against_oracle(n, top_k):
     _select_case(z, top_k)
 
 
+@pytest.mark.parametrize("rows,n,top_k", [(300, 8192, 2000), (257, 3001, 100), (700, 640, 0),
+                                          (520, 4097, 4000), (300, 8193, 2000)])
+def test_select_on_more_rows_than_compute_units(rows, n, top_k):
+    # more than 256 rows of at most 8192 ids run the 512-thread build of the row kernel, two
+    # workgroups per compute unit (8 or 16 logits per thread); 8193 ids: the 1024-thread one
+    g = np.random.default_rng(rows * 7 + n)
+    z = (g.standard_normal((rows, n)) * 3).astype(np.float32)
+    z[1, g.integers(0, n, 20)] = -np.inf
+    z[2] = np.round(z[2] * 4) / 4
+    z[3] = -np.abs(z[3]) - 100
+    z[4, :] = z[4, 0]
+    z[rows - 1] = np.round(z[rows - 1])                # ties in the last row too
+    _select_case(z, top_k)
+
+
 @pytest.mark.parametrize("n,top_k,top_p", [(1024, 0, 0.8), (1000, 100, 0.8), (1000, 0, 0.02), (1000, 0, 0.9999),
                                            (8192, 2000, 0.8), (16384, 0, 0.8), (12000, 3000, 0.95),
                                            (64000, 0, 0.8), (65536, 2000, 0.5), (40000, 0, 0.3),
@@ -157,6 +172,9 @@ def test_select_nucleus_against_oracle(n, top_k, top_p):
     (2, 6, 70000, 500, 40, [0, 37], 0.0),      # second window clipped to 3 rows
     (1, 5, 131072, 2000, 64, [9], 0.0),
     (1, 4, 100003, 0, 64, [62], 0.0),          # no filter, ragged n, window clipped to 2 rows
+    # more window rows than compute units: the two-workgroups-per-CU build of the row kernel
+    (10, 32, 2048, 200, 400, [0, 37, 74, 111, 148, 185, 222, 259, 296, 390], 0.0),
+    (33, 8, 5000, 0, 64, list(range(32)) + [60], 0.0),   # last window clipped to 4 rows
 ])
 def test_couple_draft_and_verify_against_oracle(Bn, L, n, top_k, N, pos0, top_p):
     g = np.random.default_rng(n + L)
@@ -423,6 +441,16 @@ def test_lockstep_gs_scaled_cfg_masked_batched():
     ls, st = _lockstep(wl.scaled(wl.WORKLOADS["C3"], name="C3s-gs", B=4, N=80, V=4096, d=256, v_lo=4,
                                  v_hi=1028, top_k=250), coupling="gs")
     assert st["adopt_gs"] <= max(2, 1e-3 * st["draws"])
+
+
+def test_lockstep_on_more_rows_than_compute_units():
+    # 9 x 32 = 288 window rows of 1024 ids: the 512-thread build of the row kernel, under the
+    # maximal coupling, under Gumbel sharing and under the alpha-coupling (its two hot instances)
+    kw = dict(B=9, N=72, V=4096, d=128, v_lo=4, v_hi=1028, top_k=250)
+    _lockstep(wl.scaled(wl.WORKLOADS["C3"], name="C3b", **kw))
+    ls, st = _lockstep(wl.scaled(wl.WORKLOADS["C3"], name="C3b-gs", **kw), coupling="gs")
+    assert st["adopt_gs"] <= max(2, 1e-3 * st["draws"])
+    _lockstep(wl.scaled(wl.WORKLOADS["C3"], name="C3b-alpha", **kw), coupling="mc", sjd_mix=0.5)
 
 
 def test_lockstep_gs_C1_full_and_C2_prefix():
