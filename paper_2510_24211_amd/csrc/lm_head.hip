@@ -62,6 +62,8 @@ constexpr int PITCH = BK + 8;   // LDS row pitch in bf16 elements (144 bytes)
 
 struct TrueT { static constexpr bool value = true; };
 struct FalseT { static constexpr bool value = false; };
+template <int N>
+struct IntT { static constexpr int value = N; };
 
 __device__ __forceinline__ void compiler_fence() { asm volatile("" ::: "memory"); }
 // Also a boundary for the machine scheduler, which otherwise treats loads of never-written
@@ -779,12 +781,13 @@ __global__ __launch_bounds__((SplitCfg<RBW, C, KS>::THREADS)) void lm_head_split
   const int ktq = (KT + NWAVE - 1) / NWAVE;
   const int kt_begin = wave * ktq;
   const int ntiles = max(0, min(KT, kt_begin + ktq) - kt_begin);
-  const int ntiles_pad = (ntiles + D - 1) / D * D;
-  const int rot = ntiles_pad > 0 ? (vt * 5 + wave * 3) % ntiles_pad : 0;
+  // the cyclic walk covers exactly the wavefront's tiles: the last pass of the loop below runs
+  // only as many tiles as are left (C1: 5 tiles per wavefront are one pass of 4 and one of 1)
+  const int rot = ntiles > 0 ? (vt * 5 + wave * 3) % ntiles : 0;
   auto ktile = [&](int t, bool& valid) {     // see lm_head_kernel: loads are never predicated
     int r = t + rot;
-    if (r >= ntiles_pad) r -= ntiles_pad;
-    valid = t < ntiles_pad && r < ntiles;
+    if (r >= ntiles) r -= ntiles;
+    valid = t < ntiles;
     return valid ? kt_begin + r : 0;
   };
   uint16_t* const Ws = reinterpret_cast<uint16_t*>(lds_raw) + wave * (32 + HROWS) * PITCH;
@@ -841,10 +844,12 @@ __global__ __launch_bounds__((SplitCfg<RBW, C, KS>::THREADS)) void lm_head_split
   for (int j = 0; j < D; ++j) wload(j, j);
 #pragma unroll
   for (int j = 0; j < DH; ++j) hload(j, j);
-  auto body = [&](int t0, auto pf) {           // PF false: the last pass, no loads past the end
+  // one pass over CNT <= D tiles; PF false: the last pass, no loads past the end
+  auto body = [&](int t0, auto pf, auto cnt) {
     constexpr bool PF = decltype(pf)::value;
+    constexpr int CNT = decltype(cnt)::value;
 #pragma unroll
-    for (int j = 0; j < D; ++j) {
+    for (int j = 0; j < CNT; ++j) {
       compiler_fence();
 #pragma unroll
       for (int i = 0; i < 4; ++i)
@@ -857,7 +862,7 @@ __global__ __launch_bounds__((SplitCfg<RBW, C, KS>::THREADS)) void lm_head_split
             (keep ? t4 : u32x4{0u, 0u, 0u, 0u});
       }
       if (PF) wload(j, t0 + j + D);
-      if (PF || j + DH < D) hload(j % DH, t0 + j + DH);
+      if (PF || j + DH < CNT) hload(j % DH, t0 + j + DH);
       compiler_fence();
 #pragma unroll
       for (int kk = 0; kk < BK / 16; ++kk) {
@@ -873,9 +878,18 @@ __global__ __launch_bounds__((SplitCfg<RBW, C, KS>::THREADS)) void lm_head_split
       compiler_fence();
     }
   };
-  if (ntiles_pad > 0) {
-    for (int t0 = 0; t0 < ntiles_pad - D; t0 += D) body(t0, TrueT{});
-    body(ntiles_pad - D, FalseT{});
+  {
+    const int full = ntiles / D * D, rem = ntiles - full;
+    const int prefetching = rem == 0 ? full - D : full;      // tiles of the passes that load ahead
+    for (int t0 = 0; t0 < prefetching; t0 += D) body(t0, TrueT{}, IntT<D>{});
+    if (rem == 0) {
+      if (full > 0) body(full - D, FalseT{}, IntT<D>{});
+    } else if (rem == 1) {
+      body(full, FalseT{}, IntT<1>{});
+    } else if constexpr (D > 2) {
+      if (rem == 2) body(full, FalseT{}, IntT<2>{});
+      else body(full, FalseT{}, IntT<3>{});
+    }
   }
   // the partial accumulators meet in LDS
   __syncthreads();
