@@ -141,6 +141,15 @@ def test_select_on_more_rows_than_compute_units(rows, n, top_k):
     _select_case(z, top_k)
 
 
+def test_select_nucleus_on_more_rows_than_compute_units():
+    # the nucleus instances keep 1024 threads per row whatever the number of rows
+    g = np.random.default_rng(4242)
+    z = (g.standard_normal((300, 3000)) * 3).astype(np.float32)
+    z[2] = np.round(z[2] * 4) / 4
+    z[4, :] = z[4, 0]
+    assert _select_case(z, 500, 0.8) <= 2
+
+
 @pytest.mark.parametrize("n,top_k,top_p", [(1024, 0, 0.8), (1000, 100, 0.8), (1000, 0, 0.02), (1000, 0, 0.9999),
                                            (8192, 2000, 0.8), (16384, 0, 0.8), (12000, 3000, 0.95),
                                            (64000, 0, 0.8), (65536, 2000, 0.5), (40000, 0, 0.3),
